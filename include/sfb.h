@@ -1,0 +1,146 @@
+/*
+ * libsfb: the data-parallel hot path of Sufficient Factor Broadcasting on one
+ * MI355X (gfx950).
+ *
+ * For a matrix-parameterised model  min_W (1/N) sum_i f_i(W a_i) + h(W),
+ * W in R^{J x D} (Section 2, problem (P)), the stochastic gradient of one
+ * sample is the rank-1 matrix u v^T with u = d f / d(W a), v = a (Section 2.1,
+ * "Proximal SGD").  A worker (Section 3)
+ *   1. computes the sufficient factors (SFs) of its mini-batch,
+ *   2. receives the SFs of its peers,
+ *   3. reconstructs and applies  W <- W - eta * sum_i u_i v_i^T  over all of them,
+ *   4. applies the proximal operator of h.
+ * This library is steps 1, 3 and 4; step 2 is the caller's (peer SF blocks are
+ * simply more rows of U and V).
+ *
+ * Conventions
+ *   - Row-major, dense, no padding: W[J][D] fp32; X[B][D]; U[N][J]; V[N][D]
+ *     (one SF per row: the layout in which SFs are buffered and sent,
+ *     Section 4.2).
+ *   - Every data pointer is a DEVICE pointer owned by the caller and must be
+ *     16-byte aligned.  The library allocates and frees no device memory; the
+ *     scratch it needs is the workspace the caller sets.
+ *   - Every call only enqueues kernels on the context's stream and returns; no
+ *     host synchronisation.  Results are valid once the caller has synchronised
+ *     that stream.  Calls on one context are ordered; a context must not be used
+ *     from two host threads at once.
+ *   - Return value: 0 on success, a negative sfb_status otherwise.  Nothing is
+ *     enqueued when an argument check fails.  Labels outside [0, J) are a caller
+ *     bug and are not checked on the device.
+ *   - The library never divides by the mini-batch size: the 1/K of Section 3
+ *     ("Mini-batch proximal SGD") is folded into eta by the caller.
+ */
+#ifndef SFB_H
+#define SFB_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sfb_ctx sfb_ctx; /* opaque: device id, stream, workspace, last HIP error */
+
+typedef enum { SFB_MLR = 0, SFB_DML = 1, SFB_SC = 2 } sfb_model;
+typedef enum { SFB_F32 = 0, SFB_BF16 = 1 } sfb_dtype;
+typedef enum { SFB_PROX_PROJECT = 0, SFB_PROX_NORMALIZE = 1 } sfb_prox_mode;
+
+typedef enum {
+    SFB_OK = 0,
+    SFB_EINVAL = -1, /* null pointer, bad shape, bad enum, misaligned pointer, unsupported dtype mix */
+    SFB_ENOWS = -2,  /* workspace missing or smaller than sfb_workspace_bytes() */
+    SFB_EHIP = -3    /* a HIP call failed; sfb_last_hip_error() has the code */
+} sfb_status;
+
+/* One mini-batch.  Pointers are device pointers; the struct itself is host memory. */
+typedef struct {
+    const void* X;       /* [B][D] of in_dtype.  MLR: features.  DML: first points.  SC: samples. */
+    const void* Y;       /* MLR: int32 labels [B] in [0,J).  DML: second points [B][D] of in_dtype.  SC: NULL. */
+    const int8_t* sim;   /* DML: +1 similar / -1 dissimilar, [B].  Otherwise NULL. */
+    int64_t B;           /* samples (pairs) in the batch, >= 0 */
+    int32_t in_dtype;    /* sfb_dtype of X (and of DML's Y) */
+    int32_t sf_dtype;    /* sfb_dtype of the U and V outputs */
+    float lambda;        /* SC: l1 weight */
+    int32_t ista_iters;  /* SC: ISTA iterations */
+    int32_t power_iters; /* SC: power iterations for the step size 1/L (>= 1) */
+    float margin;        /* DML: hinge margin */
+} sfb_batch;
+
+/* Creates a context bound to HIP device `device_id` and to `hip_stream`
+ * (a hipStream_t passed as void*; NULL = the device's default stream). */
+int sfb_create(sfb_ctx** out, int device_id, void* hip_stream);
+int sfb_destroy(sfb_ctx* ctx);
+
+/* Bytes of device scratch sfb_compute_sf needs for this model/shape/batch
+ * (0 is possible; negative sfb_status on bad arguments).  sfb_apply and
+ * sfb_prox_rows need none. */
+int64_t sfb_workspace_bytes(int32_t model, int64_t J, int64_t D, const sfb_batch* batch);
+
+/* Hands the context a caller-allocated device buffer (256-byte aligned) to use
+ * as scratch until replaced.  The library never frees it.  Its contents are
+ * undefined after any call. */
+int sfb_set_workspace(sfb_ctx* ctx, void* dev_ptr, int64_t bytes);
+
+/*
+ * Sufficient factors of one mini-batch at parameters W (Section 2.1: u is the
+ * derivative of f with respect to W a, v = a).  Outputs U [B][J], V [B][D] of
+ * batch->sf_dtype.
+ *
+ *   SFB_MLR (Section 1; Figure 2): multiclass logistic loss.
+ *       u_i = softmax(W x_i) - onehot(y_i),  v_i = x_i.
+ *       If V is NULL or V == X nothing is written for V (the caller passes X as
+ *       V to sfb_apply).  in_dtype F32 -> sf_dtype F32; in_dtype BF16 ->
+ *       sf_dtype BF16 (W is rounded to bf16 on the fly, fp32 accumulate).
+ *   SFB_DML (Section 2, "Distance metric learning"): a_i = x_i - y_i, q_i = W a_i.
+ *       similar pair: f = ||q||^2, u = 2 q.  dissimilar pair: f = max(0, margin - ||q||^2),
+ *       u = -2 q if ||q||^2 < margin (strictly) else 0.  v_i = a_i.
+ *       Rows of U of inactive pairs are zero (shapes stay static); *n_active
+ *       (device int32, may be NULL) receives the number of pairs with u != 0.
+ *       fp32 only.  Here J is the latent dimension (rows of W).
+ *   SFB_SC (Section 2, "Sparse coding"; Figure 3): rows of W are basis vectors;
+ *       the code a_i minimises 1/2||x_i - W^T a||^2 + lambda||a||_1 approximately by
+ *       ista_iters ISTA iterations from a = 0 with step 1/L, L = the norm estimate
+ *       after power_iters power iterations on W^T W started from the constant
+ *       unit vector.  u_i = a_i, v_i = x_i - W^T a_i; the descent step is
+ *       sfb_apply with NEGATIVE eta (W += |eta| U^T V).  fp32 only.
+ *
+ * W, X, Y are not modified.
+ */
+int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64_t D,
+                   const sfb_batch* batch, void* U, void* V, int32_t* n_active);
+
+/*
+ * Reconstructs and applies the summed rank-1 updates of N sufficient-factor
+ * pairs (Section 3: W_p <- W_p - sum_q u_q v_q^T; Section 2.1: W <- W - eta dW):
+ *       W[j][d] <- W[j][d] - eta * sum_{i<N} U[i][j] * V[i][d].
+ * U [N][J] and V [N][D] are of sf_dtype (local and peer SF blocks concatenated
+ * by rows, or one call per block: the results agree to rounding).  The
+ * accumulation is fp32; each element of W is read and written exactly once by
+ * exactly one workgroup, so the result is bit-reproducible.  eta may be
+ * negative.  N == 0 is a no-op.  U and V are not modified.
+ */
+int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const void* V,
+              int64_t N, int32_t sf_dtype, float eta);
+
+/*
+ * Proximal operator of sparse coding's norm constraint (Figure 3, "prox"), on
+ * the rows of W (the basis vectors in this library's orientation):
+ *   SFB_PROX_PROJECT:   w_j <- w_j / ||w_j||  if ||w_j|| > 1, else unchanged;
+ *   SFB_PROX_NORMALIZE: w_j <- w_j / ||w_j||  if ||w_j|| > 0.
+ */
+int sfb_prox_rows(sfb_ctx* ctx, float* W, int64_t J, int64_t D, int32_t mode);
+
+/* Static description of a status code. */
+const char* sfb_strerror(int code);
+/* hipError_t (as int) of the last failed HIP call on this context, 0 if none. */
+int sfb_last_hip_error(const sfb_ctx* ctx);
+/* Library version, "major.minor". */
+const char* sfb_version(void);
+/* Benchmark knob: picks a tile variant of the bf16 forward / apply kernels
+ * (process-wide; -1 = the default).  Every variant computes the same sums. */
+void sfb_tune_bf16_variant(int forward_variant, int apply_variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SFB_H */

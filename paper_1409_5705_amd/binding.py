@@ -1,0 +1,208 @@
+"""ctypes binding of libsfb's C-ABI (include/sfb.h).
+
+Argument marshalling only: torch tensors supply device memory and the stream;
+every step of the path runs in the library's kernels.  There is no fallback:
+if the shared library is missing, importing this module's functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsfb.so")
+
+SFB_MLR, SFB_DML, SFB_SC = 0, 1, 2
+SFB_F32, SFB_BF16 = 0, 1
+SFB_PROX_PROJECT, SFB_PROX_NORMALIZE = 0, 1
+SFB_OK, SFB_EINVAL, SFB_ENOWS, SFB_EHIP = 0, -1, -2, -3
+
+
+class sfb_batch(ctypes.Structure):
+    _fields_ = [
+        ("X", ctypes.c_void_p),
+        ("Y", ctypes.c_void_p),
+        ("sim", ctypes.c_void_p),
+        ("B", ctypes.c_int64),
+        ("in_dtype", ctypes.c_int32),
+        ("sf_dtype", ctypes.c_int32),
+        ("lambda_", ctypes.c_float),
+        ("ista_iters", ctypes.c_int32),
+        ("power_iters", ctypes.c_int32),
+        ("margin", ctypes.c_float),
+    ]
+
+
+class SfbError(RuntimeError):
+    def __init__(self, code, what, hip=0):
+        self.code = code
+        self.hip = hip
+        super().__init__("%s failed: %d (%s)%s" % (what, code, strerror(code), " hip=%d" % hip if hip else ""))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libsfb.so is not built (%s); run __graft_entry__.build() or "
+                "python paper_1409_5705_amd/build.py" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+        L.sfb_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, vp]
+        L.sfb_create.restype = ctypes.c_int
+        L.sfb_destroy.argtypes = [vp]
+        L.sfb_destroy.restype = ctypes.c_int
+        L.sfb_workspace_bytes.argtypes = [i32, i64, i64, ctypes.POINTER(sfb_batch)]
+        L.sfb_workspace_bytes.restype = i64
+        L.sfb_set_workspace.argtypes = [vp, vp, i64]
+        L.sfb_set_workspace.restype = ctypes.c_int
+        L.sfb_compute_sf.argtypes = [vp, i32, vp, i64, i64, ctypes.POINTER(sfb_batch), vp, vp, vp]
+        L.sfb_compute_sf.restype = ctypes.c_int
+        L.sfb_apply.argtypes = [vp, vp, i64, i64, vp, vp, i64, i32, ctypes.c_float]
+        L.sfb_apply.restype = ctypes.c_int
+        L.sfb_prox_rows.argtypes = [vp, vp, i64, i64, i32]
+        L.sfb_prox_rows.restype = ctypes.c_int
+        L.sfb_strerror.argtypes = [ctypes.c_int]
+        L.sfb_strerror.restype = ctypes.c_char_p
+        L.sfb_last_hip_error.argtypes = [vp]
+        L.sfb_last_hip_error.restype = ctypes.c_int
+        L.sfb_version.argtypes = []
+        L.sfb_version.restype = ctypes.c_char_p
+        L.sfb_tune_bf16_variant.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.sfb_tune_bf16_variant.restype = None
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().sfb_strerror(int(code)).decode()
+
+
+def version() -> str:
+    return lib().sfb_version().decode()
+
+
+def sfb_tune_bf16_variant(forward_variant: int = -1, apply_variant: int = -1) -> None:
+    lib().sfb_tune_bf16_variant(int(forward_variant), int(apply_variant))
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SFB_F32
+    if t.dtype == torch.bfloat16:
+        return SFB_BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def _ptr(t, name, dtype=None, shape=None):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a device tensor" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous (dense row-major)" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %r, got %r" % (name, tuple(shape), tuple(t.shape)))
+    return t.data_ptr()
+
+
+class Context:
+    """One sfb_ctx bound to a device and a stream; owns a torch workspace tensor."""
+
+    def __init__(self, device=0, stream=None):
+        self._h = ctypes.c_void_p()
+        self.device = torch.device("cuda", device) if isinstance(device, int) else torch.device(device)
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device)
+        self.stream = stream
+        rc = lib().sfb_create(ctypes.byref(self._h), self.device.index or 0, ctypes.c_void_p(stream.cuda_stream))
+        if rc != SFB_OK:
+            raise SfbError(rc, "sfb_create")
+        self._ws = None
+
+    def close(self):
+        if self._h:
+            lib().sfb_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc, what):
+        if rc != SFB_OK:
+            raise SfbError(rc, what, lib().sfb_last_hip_error(self._h))
+
+    # -- workspace ---------------------------------------------------------
+    def sfb_workspace_bytes(self, model, J, D, batch: sfb_batch) -> int:
+        n = lib().sfb_workspace_bytes(model, J, D, ctypes.byref(batch))
+        if n < 0:
+            raise SfbError(int(n), "sfb_workspace_bytes")
+        return int(n)
+
+    def sfb_set_workspace(self, tensor):
+        """Use `tensor` (uint8, device) as scratch; None clears it."""
+        if tensor is None:
+            self._check(lib().sfb_set_workspace(self._h, None, 0), "sfb_set_workspace")
+        else:
+            self._check(lib().sfb_set_workspace(self._h, tensor.data_ptr(), tensor.numel() * tensor.element_size()),
+                        "sfb_set_workspace")
+        self._ws = tensor
+
+    def _ensure_workspace(self, model, J, D, batch):
+        need = self.sfb_workspace_bytes(model, J, D, batch)
+        have = 0 if self._ws is None else self._ws.numel()
+        if need > have:
+            self.sfb_set_workspace(torch.empty(need, dtype=torch.uint8, device=self.device))
+
+    # -- the calls of the path --------------------------------------------
+    def sfb_compute_sf(self, model, W, X, Y=None, sim=None, U=None, V=None, n_active=None,
+                       lam=0.1, ista_iters=20, power_iters=10, margin=1.0):
+        """Enqueues the SF computation; U (and V) must be preallocated device tensors."""
+        J, D = W.shape
+        B = X.shape[0]
+        b = sfb_batch()
+        b.X = _ptr(X, "X", shape=(B, D))
+        b.B = B
+        b.in_dtype = _dtype_code(X)
+        b.sf_dtype = _dtype_code(U)
+        b.lambda_ = lam
+        b.ista_iters = ista_iters
+        b.power_iters = power_iters
+        b.margin = margin
+        if model == SFB_MLR:
+            b.Y = _ptr(Y, "Y (labels)", dtype=torch.int32, shape=(B,))
+        elif model == SFB_DML:
+            b.Y = _ptr(Y, "Y", dtype=X.dtype, shape=(B, D))
+            b.sim = _ptr(sim, "sim", dtype=torch.int8, shape=(B,))
+        self._ensure_workspace(model, J, D, b)
+        rc = lib().sfb_compute_sf(self._h, model, _ptr(W, "W", dtype=torch.float32), J, D, ctypes.byref(b),
+                                  _ptr(U, "U", shape=(B, J)),
+                                  _ptr(V, "V", shape=(B, D)) if V is not None else None,
+                                  _ptr(n_active, "n_active", dtype=torch.int32) if n_active is not None else None)
+        self._check(rc, "sfb_compute_sf")
+
+    def sfb_apply(self, W, U, V, eta):
+        """Enqueues W -= eta * U^T V (in place)."""
+        J, D = W.shape
+        N = U.shape[0]
+        if U.dtype != V.dtype:
+            raise TypeError("U and V must share a dtype")
+        rc = lib().sfb_apply(self._h, _ptr(W, "W", dtype=torch.float32), J, D, _ptr(U, "U", shape=(N, J)),
+                             _ptr(V, "V", shape=(N, D)), N, _dtype_code(U), float(eta))
+        self._check(rc, "sfb_apply")
+
+    def sfb_prox_rows(self, W, mode=SFB_PROX_PROJECT):
+        J, D = W.shape
+        self._check(lib().sfb_prox_rows(self._h, _ptr(W, "W", dtype=torch.float32), J, D, mode), "sfb_prox_rows")

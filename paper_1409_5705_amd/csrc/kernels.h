@@ -1,0 +1,74 @@
+// Internal (C++) launch interface between the C-ABI layer and the HIP kernels.
+// Every function only enqueues work on `stream` and returns the launch status.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sfb {
+
+// ---------------------------------------------------------------------------
+// fp32 MFMA GEMM family:  acc[m][n] = sum_k A(m,k) * B(n,k), followed by an
+// epilogue that writes C[m*ldc + n].
+//   operand layout "k-contiguous": A(m,k) = A[m*lda + k]
+//   operand layout "k-strided":    A(m,k) = A[k*lda + m]
+// ---------------------------------------------------------------------------
+enum GemmEpilogue : int {
+    EPI_STORE = 0,   // C = acc
+    EPI_RMW = 1,     // C = C - eta * acc                      (rank-1 update sum applied to W)
+    EPI_RESID = 2,   // C = aux - acc                          (sparse-coding residual x - W^T a)
+    EPI_SHRINK = 3,  // C = soft(aux + acc / L, lambda / L)    (one ISTA step), L read from *L_ptr
+};
+
+struct GemmF32Args {
+    const float* A;
+    int64_t lda;
+    bool a_kstrided;
+    const float* B;
+    int64_t ldb;
+    bool b_kstrided;
+    float* C;
+    int64_t ldc;
+    int64_t M, N, K;
+    int epilogue;
+    float eta;           // EPI_RMW
+    const float* aux;    // EPI_RESID / EPI_SHRINK, same leading dimension as C; may alias C
+    const float* L_ptr;  // EPI_SHRINK: device scalar
+    float lambda;        // EPI_SHRINK
+};
+hipError_t launch_gemm_f32(const GemmF32Args& a, hipStream_t stream);
+
+// ---------------------------------------------------------------------------
+// bf16 MFMA kernels of the large MLR path (fp32 accumulate).
+// ---------------------------------------------------------------------------
+// Z[b][j] = sum_d X[b][d] * bf16(W[j][d]);  X bf16 [B][D], W fp32 [J][D], Z fp32 [B][J].
+hipError_t launch_mlr_forward_bf16(const uint16_t* X, const float* W, float* Z,
+                                   int64_t B, int64_t J, int64_t D, hipStream_t stream);
+// W[j][d] -= eta * sum_i U[i][j] * V[i][d];  U bf16 [N][J], V bf16 [N][D], W fp32 [J][D].
+hipError_t launch_apply_bf16(float* W, const uint16_t* U, const uint16_t* V,
+                             int64_t N, int64_t J, int64_t D, float eta, hipStream_t stream);
+// Selects a tile variant of the two kernels above (benchmark sweeps); -1 = default.
+void set_bf16_variant(int forward_variant, int apply_variant);
+
+// ---------------------------------------------------------------------------
+// Row-wise kernels.
+// ---------------------------------------------------------------------------
+// U[i][j] = exp(Z[i][j] - max_i) / sum_i - [j == y[i]];  out_bf16 selects the U dtype.
+hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool out_bf16,
+                              int64_t B, int64_t J, hipStream_t stream);
+// V = X - Y (elementwise, n elements).
+hipError_t launch_diff(const float* X, const float* Y, float* V, int64_t n, hipStream_t stream);
+// DML coefficient: d = ||Q_i||^2; c = +2 (sim>0), -2 (sim<=0 and d<margin), else 0; U_i = c Q_i.
+// n_active (nullable) must have been zeroed; it is incremented once per active row.
+hipError_t launch_dml_scale(const float* Q, const int8_t* sim, float* U, int32_t* n_active,
+                            float margin, int64_t B, int64_t K, hipStream_t stream);
+// Fill n 32-bit words with `value`.
+hipError_t launch_fill_u32(void* p, uint32_t value, int64_t n, hipStream_t stream);
+// Row projection / normalisation of W[J][D].
+hipError_t launch_prox_rows(float* W, int64_t J, int64_t D, int mode, hipStream_t stream);
+// Power iteration on W^T W: writes the norm estimate to *L_out (device).
+// scratch: float[D (b) + J (c) + chunks*D (partials) + D (g)] with chunks = power_chunks(J).
+int64_t power_chunks(int64_t J);
+hipError_t launch_power_iteration(const float* W, int64_t J, int64_t D, int iters, float* scratch,
+                                  float* L_out, hipStream_t stream);
+
+}  // namespace sfb

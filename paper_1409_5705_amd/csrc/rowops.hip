@@ -1,0 +1,304 @@
+// Row-wise and elementwise kernels around the GEMMs: the softmax/label step of
+// multiclass logistic regression, the pair difference and hinge coefficient of
+// distance metric learning, the power iteration and the row projection of
+// sparse coding.  All are HBM-bound streaming kernels with wavefront (64-lane)
+// shuffle reductions.
+#include "kernels.h"
+
+namespace sfb {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+// Block reductions; `sm` has NT/64 floats.  Every thread gets the result.
+template <int NT>
+__device__ __forceinline__ float block_sum(float v, float* sm)
+{
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = 0.f;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) r += sm[w];
+    return r;
+}
+template <int NT>
+__device__ __forceinline__ float block_max(float v, float* sm)
+{
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = sm[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) r = fmaxf(r, sm[w]);
+    return r;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
+{
+    floatx2 f = {a, b};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// ---------------------------------------------------------------------------
+// MLR: u = softmax(z) - onehot(y).  One workgroup per sample; three passes over
+// the row (max, sum of exponentials, normalise + label + store).
+// ---------------------------------------------------------------------------
+template <int NT, bool OUT_BF16>
+__global__ __launch_bounds__(NT) void mlr_softmax_kernel(const float* __restrict__ Z, const int32_t* __restrict__ y,
+                                                         void* __restrict__ Uv, int64_t J, int vec)
+{
+    __shared__ float sm[NT / 64];
+    const int64_t row = blockIdx.x;
+    const float* z = Z + row * J;
+    const int tid = threadIdx.x;
+    const int64_t J4 = vec ? J / 4 : 0;
+
+    float m = -INFINITY;
+    for (int64_t q = tid; q < J4; q += NT) {
+        const floatx4 v = reinterpret_cast<const floatx4*>(z)[q];
+        m = fmaxf(fmaxf(m, fmaxf(v[0], v[1])), fmaxf(v[2], v[3]));
+    }
+    for (int64_t j = J4 * 4 + tid; j < J; j += NT) m = fmaxf(m, z[j]);
+    m = block_max<NT>(m, sm);
+
+    float s = 0.f;
+    for (int64_t q = tid; q < J4; q += NT) {
+        const floatx4 v = reinterpret_cast<const floatx4*>(z)[q];
+        s += (expf(v[0] - m) + expf(v[1] - m)) + (expf(v[2] - m) + expf(v[3] - m));
+    }
+    for (int64_t j = J4 * 4 + tid; j < J; j += NT) s += expf(z[j] - m);
+    s = block_sum<NT>(s, sm);
+    const float inv = 1.0f / s;
+
+    const int64_t lab = y[row];
+    for (int64_t q = tid; q < J4; q += NT) {
+        const floatx4 v = reinterpret_cast<const floatx4*>(z)[q];
+        floatx4 p;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) p[e] = expf(v[e] - m) * inv - ((q * 4 + e == lab) ? 1.0f : 0.0f);
+        if (OUT_BF16) {
+            uint2 o;
+            o.x = pack_bf16(p[0], p[1]);
+            o.y = pack_bf16(p[2], p[3]);
+            reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(Uv) + row * J)[q] = o;
+        } else {
+            reinterpret_cast<floatx4*>(reinterpret_cast<float*>(Uv) + row * J)[q] = p;
+        }
+    }
+    for (int64_t j = J4 * 4 + tid; j < J; j += NT) {
+        const float p = expf(z[j] - m) * inv - ((j == lab) ? 1.0f : 0.0f);
+        if (OUT_BF16) {
+            reinterpret_cast<uint16_t*>(Uv)[row * J + j] = (uint16_t)(pack_bf16(p, 0.f) & 0xffffu);
+        } else {
+            reinterpret_cast<float*>(Uv)[row * J + j] = p;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void diff_kernel(const float* __restrict__ X, const float* __restrict__ Y,
+                                                   float* __restrict__ V, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) V[i] = X[i] - Y[i];
+}
+
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ p, uint32_t value, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) p[i] = value;
+}
+
+// DML: one workgroup per pair.
+__global__ __launch_bounds__(256) void dml_scale_kernel(const float* __restrict__ Q, const int8_t* __restrict__ sim,
+                                                        float* __restrict__ U, int32_t* __restrict__ n_active,
+                                                        float margin, int64_t K)
+{
+    __shared__ float sm[4];
+    const int64_t row = blockIdx.x;
+    const float* q = Q + row * K;
+    float d = 0.f;
+    for (int64_t k = threadIdx.x; k < K; k += 256) d += q[k] * q[k];
+    d = block_sum<256>(d, sm);
+    float c;
+    if (sim[row] > 0)
+        c = 2.0f;
+    else
+        c = (d < margin) ? -2.0f : 0.0f;
+    for (int64_t k = threadIdx.x; k < K; k += 256) U[row * K + k] = c * q[k];
+    if (threadIdx.x == 0 && c != 0.0f && n_active) atomicAdd(n_active, 1);
+}
+
+// Prox of the unit-ball constraint on each row.
+__global__ __launch_bounds__(256) void prox_rows_kernel(float* __restrict__ W, int64_t D, int mode)
+{
+    __shared__ float sm[4];
+    float* w = W + (int64_t)blockIdx.x * D;
+    float nn = 0.f;
+    for (int64_t d = threadIdx.x; d < D; d += 256) nn += w[d] * w[d];
+    nn = block_sum<256>(nn, sm);
+    const float nrm = sqrtf(nn);
+    const bool scale = (mode == 0) ? (nrm > 1.0f) : (nrm > 0.0f);
+    if (scale)
+        for (int64_t d = threadIdx.x; d < D; d += 256) w[d] = w[d] / nrm;
+}
+
+// ---------------------------------------------------------------------------
+// Power iteration on W^T W (three kernels per iteration).
+// ---------------------------------------------------------------------------
+// c[j] = sum_d W[j][d] b[d]; one wavefront per row.
+__global__ __launch_bounds__(256) void gemv_rows_kernel(const float* __restrict__ W, const float* __restrict__ b,
+                                                        float* __restrict__ c, int64_t J, int64_t D)
+{
+    const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= J) return;
+    const int lane = threadIdx.x & 63;
+    float s = 0.f;
+    for (int64_t d = lane; d < D; d += 64) s += W[j * D + d] * b[d];
+    s = wave_sum(s);
+    if (lane == 0) c[j] = s;
+}
+// part[chunk][d] = sum over the chunk's rows of W[j][d] c[j].
+__global__ __launch_bounds__(256) void gemv_cols_partial_kernel(const float* __restrict__ W,
+                                                                const float* __restrict__ c,
+                                                                float* __restrict__ part, int64_t J, int64_t D,
+                                                                int64_t rows_per_chunk)
+{
+    const int64_t d = (int64_t)blockIdx.y * 256 + threadIdx.x;
+    if (d >= D) return;
+    const int64_t j0 = (int64_t)blockIdx.x * rows_per_chunk;
+    const int64_t j1 = j0 + rows_per_chunk < J ? j0 + rows_per_chunk : J;
+    float s = 0.f;
+    for (int64_t j = j0; j < j1; ++j) s += W[j * D + d] * c[j];
+    part[(int64_t)blockIdx.x * D + d] = s;
+}
+// g = sum of partials (fixed order); L = ||g||; b = g / L.  One workgroup.
+__global__ __launch_bounds__(1024) void power_finish_kernel(const float* __restrict__ part, float* __restrict__ g,
+                                                            float* __restrict__ b, float* __restrict__ L_out,
+                                                            int64_t D, int64_t chunks)
+{
+    __shared__ float sm[16];
+    float nn = 0.f;
+    for (int64_t d = threadIdx.x; d < D; d += 1024) {
+        float s = 0.f;
+        for (int64_t ch = 0; ch < chunks; ++ch) s += part[ch * D + d];
+        g[d] = s;
+        nn += s * s;
+    }
+    nn = block_sum<1024>(nn, sm);
+    const float L = sqrtf(nn);
+    if (threadIdx.x == 0) L_out[0] = L;
+    for (int64_t d = threadIdx.x; d < D; d += 1024) b[d] = g[d] / L;
+}
+
+unsigned grid_for(int64_t n)
+{
+    int64_t g = (n + 255) / 256;
+    if (g > 65536) g = 65536;
+    if (g < 1) g = 1;
+    return (unsigned)g;
+}
+
+}  // namespace
+
+hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool out_bf16, int64_t B, int64_t J,
+                              hipStream_t stream)
+{
+    if (B <= 0 || J <= 0) return hipSuccess;
+    // Vector path: rows of Z (and of U) must start 16-byte (8-byte for bf16 U) aligned.
+    const int vec = (J % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0) &&
+                    (reinterpret_cast<uintptr_t>(U) % 16 == 0);
+    const dim3 grid((unsigned)B);
+    if (J > 16384) {
+        if (out_bf16)
+            hipLaunchKernelGGL((mlr_softmax_kernel<1024, true>), grid, dim3(1024), 0, stream, Z, y, U, J, vec);
+        else
+            hipLaunchKernelGGL((mlr_softmax_kernel<1024, false>), grid, dim3(1024), 0, stream, Z, y, U, J, vec);
+    } else {
+        if (out_bf16)
+            hipLaunchKernelGGL((mlr_softmax_kernel<256, true>), grid, dim3(256), 0, stream, Z, y, U, J, vec);
+        else
+            hipLaunchKernelGGL((mlr_softmax_kernel<256, false>), grid, dim3(256), 0, stream, Z, y, U, J, vec);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_diff(const float* X, const float* Y, float* V, int64_t n, hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(diff_kernel, dim3(grid_for(n)), dim3(256), 0, stream, X, Y, V, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(void* p, uint32_t value, int64_t n, hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(n)), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(p),
+                       value, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_dml_scale(const float* Q, const int8_t* sim, float* U, int32_t* n_active, float margin, int64_t B,
+                            int64_t K, hipStream_t stream)
+{
+    if (B <= 0) return hipSuccess;
+    hipLaunchKernelGGL(dml_scale_kernel, dim3((unsigned)B), dim3(256), 0, stream, Q, sim, U, n_active, margin, K);
+    return hipGetLastError();
+}
+
+hipError_t launch_prox_rows(float* W, int64_t J, int64_t D, int mode, hipStream_t stream)
+{
+    if (J <= 0 || D <= 0) return hipSuccess;
+    hipLaunchKernelGGL(prox_rows_kernel, dim3((unsigned)J), dim3(256), 0, stream, W, D, mode);
+    return hipGetLastError();
+}
+
+int64_t power_chunks(int64_t J)
+{
+    int64_t ch = (J + 63) / 64;
+    if (ch > 1024) ch = 1024;
+    if (ch < 1) ch = 1;
+    return ch;
+}
+
+hipError_t launch_power_iteration(const float* W, int64_t J, int64_t D, int iters, float* scratch, float* L_out,
+                                  hipStream_t stream)
+{
+    const int64_t chunks = power_chunks(J);
+    const int64_t rows_per_chunk = (J + chunks - 1) / chunks;
+    float* b = scratch;
+    float* c = b + D;
+    float* part = c + J;
+    float* g = part + chunks * D;
+    const float b0 = 1.0f / sqrtf((float)D);
+    hipError_t e = launch_fill_u32(b, __builtin_bit_cast(uint32_t, b0), D, stream);
+    if (e != hipSuccess) return e;
+    for (int it = 0; it < iters; ++it) {
+        hipLaunchKernelGGL(gemv_rows_kernel, dim3((unsigned)((J + 3) / 4)), dim3(256), 0, stream, W, b, c, J, D);
+        hipLaunchKernelGGL(gemv_cols_partial_kernel, dim3((unsigned)chunks, (unsigned)((D + 255) / 256)), dim3(256),
+                           0, stream, W, c, part, J, D, rows_per_chunk);
+        hipLaunchKernelGGL(power_finish_kernel, dim3(1), dim3(1024), 0, stream, part, g, b, L_out, D, chunks);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace sfb

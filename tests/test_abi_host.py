@@ -1,0 +1,88 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, it exports
+every symbol the header declares, and the argument logic that runs before any
+device call behaves as documented."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def sfb():
+    import paper_1409_5705_amd as m
+    if not os.path.exists(m.binding.LIB_PATH):
+        from paper_1409_5705_amd.build import build_library
+        build_library()
+    m.lib()
+    return m
+
+
+def test_exports_every_declared_symbol(sfb):
+    hdr = open(os.path.join(ROOT, "include", "sfb.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = sorted(set(re.findall(r"\b(sfb_[a-z0-9_]+)\s*\(", hdr)))
+    assert {"sfb_create", "sfb_destroy", "sfb_compute_sf", "sfb_apply", "sfb_prox_rows",
+            "sfb_workspace_bytes", "sfb_set_workspace", "sfb_strerror"} <= set(names)
+    L = sfb.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_strerror_and_version(sfb):
+    assert sfb.strerror(0) == "success"
+    assert "workspace" in sfb.strerror(sfb.SFB_ENOWS)
+    assert "invalid" in sfb.strerror(sfb.SFB_EINVAL)
+    assert re.match(r"^\d+\.\d+$", sfb.version())
+
+
+def _batch(sfb, B=8, in_dtype=0, sf_dtype=0, ista=20, power=10, lam=0.1):
+    b = sfb.sfb_batch()
+    b.B = B
+    b.in_dtype = in_dtype
+    b.sf_dtype = sf_dtype
+    b.ista_iters = ista
+    b.power_iters = power
+    b.lambda_ = lam
+    b.margin = 1.0
+    return b
+
+
+def test_workspace_bytes_logic(sfb):
+    L = sfb.lib()
+    wb = lambda model, J, D, b: L.sfb_workspace_bytes(model, J, D, ctypes.byref(b))
+    assert wb(sfb.SFB_MLR, 100, 64, _batch(sfb, B=8)) >= 8 * 100 * 4
+    assert wb(sfb.SFB_MLR, 100, 64, _batch(sfb, B=8)) % 256 == 0
+    assert wb(sfb.SFB_DML, 16, 64, _batch(sfb, B=4)) >= 4 * 16 * 4
+    assert wb(sfb.SFB_SC, 128, 64, _batch(sfb)) > (64 + 128 + 64) * 4
+    # bad arguments are reported, not crashed on
+    assert wb(sfb.SFB_MLR, 0, 64, _batch(sfb)) == sfb.SFB_EINVAL
+    assert wb(7, 10, 64, _batch(sfb)) == sfb.SFB_EINVAL
+    assert wb(sfb.SFB_MLR, 100, 64, _batch(sfb, in_dtype=1, sf_dtype=0)) == sfb.SFB_EINVAL
+    assert wb(sfb.SFB_MLR, 100, 60, _batch(sfb, in_dtype=1, sf_dtype=1)) == sfb.SFB_EINVAL   # D % 8
+    assert wb(sfb.SFB_DML, 16, 64, _batch(sfb, in_dtype=1, sf_dtype=1)) == sfb.SFB_EINVAL    # fp32 only
+    assert wb(sfb.SFB_SC, 16, 64, _batch(sfb, power=0)) == sfb.SFB_EINVAL
+    assert L.sfb_workspace_bytes(sfb.SFB_MLR, 10, 10, None) == sfb.SFB_EINVAL
+
+
+def test_null_context_is_rejected(sfb):
+    L = sfb.lib()
+    assert L.sfb_apply(None, None, 4, 4, None, None, 1, 0, ctypes.c_float(0.1)) == sfb.SFB_EINVAL
+    assert L.sfb_prox_rows(None, None, 4, 4, 0) == sfb.SFB_EINVAL
+    assert L.sfb_destroy(None) == sfb.SFB_EINVAL
+    assert L.sfb_create(None, 0, None) == sfb.SFB_EINVAL
+
+
+def test_product_never_imports_oracle():
+    pkg = os.path.join(ROOT, "paper_1409_5705_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                txt = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in txt.lower(), os.path.join(dirpath, f)
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            txt = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_1409_5705_amd" not in txt and "libsfb.so" not in txt

@@ -1,0 +1,103 @@
+"""GPU parity at the full size of the headline workload (MLR, J=325,000 classes,
+D=10,000 features, B=1024, bf16 inputs, fp32 W), in the launch configuration the
+bench times.  The oracle cannot finish the whole step in seconds, so:
+
+ * SFs: all J entries of u for a few sampled samples, computed one by one by the
+   oracle from the same W and X;
+ * reconstruction: sfb_apply on W = 0 with generated factors, compared on a
+   random subset of rows of W (the oracle's apply is separable over rows);
+ * a whole-matrix property that holds at any size: column sums of the update
+   equal sum_i (sum_j U[i][j]) V[i][d].
+"""
+import numpy as np
+import pytest
+
+import sfb_synth as S
+from parity import TOL_BF16, TOL_F32, rel_err
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+CFG = S.CONFIGS["mlr_large_bf16"]
+
+
+@pytest.fixture(scope="module")
+def sfb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1409_5705_amd as m
+    m.lib()
+    return m
+
+
+@pytest.fixture(scope="module")
+def big(sfb):
+    J, D, B = CFG["J"], CFG["D"], CFG["B"]
+    print("large: generating W on device", flush=True)
+    gen = torch.Generator(device="cuda:0"); gen.manual_seed(0)
+    W = torch.randn((J, D), dtype=torch.float32, device="cuda:0", generator=gen) * CFG["sigma"]
+    X, y = S.mlr_batch(J, D, B, seed=0, zero_frac=CFG["zero_frac"], bf16=True)
+    Xd = torch.from_numpy(S.bf16_bits(X)).to("cuda:0").view(torch.bfloat16)
+    yd = torch.from_numpy(y).to("cuda:0")
+    ctx = sfb.Context(0)
+    yield dict(W=W, X=X, y=y, Xd=Xd, yd=yd, ctx=ctx, J=J, D=D, B=B)
+    ctx.close()
+
+
+@pytest.mark.timeout(600)
+def test_large_mlr_sf_sampled(big, sfb, oracle):
+    J, D, B = big["J"], big["D"], big["B"]
+    U = torch.empty((B, J), dtype=torch.bfloat16, device="cuda:0")
+    print("large: compute_sf", flush=True)
+    big["ctx"].sfb_compute_sf(sfb.SFB_MLR, big["W"], big["Xd"], Y=big["yd"], U=U)
+    torch.cuda.synchronize()
+    rows = np.array([0, 1, 127, 128, 500, 777, 1022, 1023])
+    print("large: W to host", flush=True)
+    Wh = big["W"].cpu().numpy()
+    print("large: oracle on %d samples" % len(rows), flush=True)
+    Uo, _ = oracle.mlr_sf(Wh, big["X"][rows], big["y"][rows])
+    del Wh
+    Ug = U[torch.from_numpy(rows).to("cuda:0")].float().cpu().numpy()
+    err = rel_err(Ug, Uo)
+    print("large: U err", err, flush=True)
+    assert err <= TOL_BF16
+    # the label entry and the zero-sum property on every sample (bf16 rounding of ~3e-6 entries)
+    s = U.float().sum(dim=1).cpu().numpy()
+    assert np.max(np.abs(s)) < 2e-2
+    big["U"] = U
+
+
+@pytest.mark.timeout(600)
+def test_large_apply_reconstruction(big, sfb, oracle):
+    J, D, B = big["J"], big["D"], big["B"]
+    print("large: generating factors", flush=True)
+    g = np.random.default_rng(11)
+    # U with the magnitude mix of MLR factors: ~1/J everywhere, -1 at one label per row
+    Uh = (g.random((B, J), dtype=np.float32) * np.float32(2.0 / J))
+    Uh[np.arange(B), g.integers(0, J, B)] -= 1.0
+    Uh = S.round_to_bf16(Uh)
+    Ud = torch.from_numpy(S.bf16_bits(Uh)).to("cuda:0").view(torch.bfloat16)
+    Wz = torch.zeros((J, D), dtype=torch.float32, device="cuda:0")
+    print("large: apply", flush=True)
+    big["ctx"].sfb_apply(Wz, Ud, big["Xd"], 1.0)
+    torch.cuda.synchronize()
+    rows = np.sort(g.choice(J, size=1536, replace=False))
+    rows[:4] = [0, 1, 2, 3]; rows[-4:] = [J - 4, J - 3, J - 2, J - 1]
+    rows = np.unique(rows)
+    print("large: oracle apply on %d rows" % len(rows), flush=True)
+    ref = oracle.apply(np.zeros((len(rows), D)), Uh[:, rows], big["X"], 1.0)
+    got = Wz[torch.from_numpy(rows).to("cuda:0")].cpu().numpy()
+    err = rel_err(got, ref)
+    print("large: reconstruction err", err, flush=True)
+    assert err <= TOL_F32
+    # whole-matrix property: column sums
+    colsum = Wz.sum(dim=0, dtype=torch.float64)
+    s = Ud.double().sum(dim=1)
+    expect = -(s @ big["Xd"].double())
+    e2 = float((colsum - expect).abs().max() / expect.abs().max())
+    print("large: column-sum err", e2, flush=True)
+    assert e2 < 1e-3
+    # second application with the opposite sign restores zero (up to rounding of the sums)
+    big["ctx"].sfb_apply(Wz, Ud, big["Xd"], -1.0)
+    torch.cuda.synchronize()
+    assert float(Wz.abs().max()) == 0.0
