@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the sufficient-factor hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic batch: SF compute
+(forward contraction + softmax/label step) followed by reconstruction and
+application of the summed rank-1 updates.  Default workload: the headline one,
+multiclass logistic regression with J=325,000 classes, D=10,000 features,
+B=1024, bf16 inputs, fp32 W and accumulation.  Inputs are resident in HBM before
+the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Published MI355X peaks used for the roofline fractions.
+PEAK_HBM_GBS = 8000.0
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_F32_TFLOPS = 157.3
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline_mlr(cfg, X, y, seed):
+    """The oracle, as it stands, on a bounded sample of the workload: the first Js classes
+    (softmax over those), all B samples, full D: SF compute + apply.  Scaled to the metric's
+    unit by Js/J (both stages are linear in the number of classes)."""
+    import numpy as np
+    import oracle
+    import sfb_synth as S
+    J, D, B = cfg["J"], cfg["D"], cfg["B"]
+    Js = min(J, 8192)
+    Ws = S.normal_matrix(Js, D, cfg["sigma"], seed)
+    ys = (y % Js).astype(np.int32)
+    t0 = time.perf_counter()
+    U, V = oracle.mlr_sf(Ws, X, ys)
+    t1 = time.perf_counter()
+    oracle.apply(Ws, U, V, cfg["eta"])
+    t2 = time.perf_counter()
+    dt = t2 - t0
+    return {
+        "value": (B / dt) * (Js / J),
+        "unit": "updates/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": "first %d of %d classes (softmax over those), all %d samples, D=%d; one step = SF compute "
+                  "(%.1f s) + apply (%.1f s); rate scaled by %d/%d" % (Js, J, B, D, t1 - t0, t2 - t1, Js, J),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="mlr_large_bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--forward-variant", type=int, default=-1)
+    ap.add_argument("--apply-variant", type=int, default=-1)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (each GPU box has one GPU); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import sfb_synth as S
+    import paper_1409_5705_amd as sfb
+
+    if args.workload != "mlr_large_bf16":
+        print("unknown workload %r (bench lines exist for mlr_large_bf16 only)" % args.workload, file=sys.stderr)
+        sys.exit(2)
+    cfg = S.CONFIGS[args.workload]
+    J, D, B, eta = cfg["J"], cfg["D"], cfg["B"], cfg["eta"]
+    dev = torch.device("cuda", 0)
+    sfb.lib()
+    sfb.sfb_tune_bf16_variant(args.forward_variant, args.apply_variant)
+
+    log("bench: generating inputs (W %.1f GB on device)" % (J * D * 4 / 1e9))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+    W = torch.randn((J, D), dtype=torch.float32, device=dev, generator=gen) * cfg["sigma"]
+    n_batches = args.steps + args.warmup
+    Xs, ys, X0, y0 = [], [], None, None
+    for s in range(min(n_batches, 4)):                     # a few distinct batches, cycled
+        X, y = S.mlr_batch(J, D, B, seed=0, step=s, zero_frac=cfg["zero_frac"], bf16=True)
+        if s == 0:
+            X0, y0 = X, y
+        Xs.append(torch.from_numpy(S.bf16_bits(X)).to(dev).view(torch.bfloat16))
+        ys.append(torch.from_numpy(y).to(dev))
+    U = torch.empty((B, J), dtype=torch.bfloat16, device=dev)
+    ctx = sfb.Context(0)
+
+    def step(i):
+        Xd, yd = Xs[i % len(Xs)], ys[i % len(ys)]
+        ctx.sfb_compute_sf(sfb.SFB_MLR, W, Xd, Y=yd, U=U)   # V = X
+        ctx.sfb_apply(W, U, Xd, eta)
+
+    log("bench: warmup")
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ctx.sfb_profile_enable(True)
+    ctx.sfb_profile_collect()
+    torch.cuda.synchronize()
+    log("bench: timing %d steps" % args.steps)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = ctx.sfb_profile_collect()
+    ctx.sfb_profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    assert bool(torch.isfinite(W[:1024]).all())
+
+    # per-kernel averages from the HIP events recorded on the library's stream
+    kt = {k: v[1] / v[0] for k, v in prof.items()}          # ms per launch
+    fwd_ms = kt.get("mlr_forward_bf16", float("nan"))
+    app_ms = kt.get("apply_bf16", float("nan"))
+    smx_ms = kt.get("mlr_softmax", float("nan"))
+    gemm_flops = 2.0 * B * J * D                             # per GEMM stage
+    # algorithmic HBM bytes per launch
+    fwd_bytes = J * D * 4 + B * D * 2 + B * J * 4            # W read once, X, logits written
+    app_bytes = 2 * J * D * 4 + B * J * 2 + B * D * 2        # W read + written once, U, V
+    smx_bytes = B * J * 4 + B * J * 2                        # logits read once, U written
+    stages = {
+        "forward_gemm": {"ms": fwd_ms, "tflops": gemm_flops / fwd_ms / 1e9,
+                         "mfma_frac": gemm_flops / fwd_ms / 1e9 / PEAK_BF16_TFLOPS,
+                         "hbm_gbs": fwd_bytes / fwd_ms / 1e6, "hbm_frac": fwd_bytes / fwd_ms / 1e6 / PEAK_HBM_GBS},
+        "softmax": {"ms": smx_ms, "hbm_gbs": smx_bytes / smx_ms / 1e6,
+                    "hbm_frac": smx_bytes / smx_ms / 1e6 / PEAK_HBM_GBS},
+        "apply_gemm": {"ms": app_ms, "tflops": gemm_flops / app_ms / 1e9,
+                       "mfma_frac": gemm_flops / app_ms / 1e9 / PEAK_BF16_TFLOPS,
+                       "hbm_gbs": app_bytes / app_ms / 1e6, "hbm_frac": app_bytes / app_ms / 1e6 / PEAK_HBM_GBS},
+    }
+    # Roofline of the dominant kernel.  At this shape the forward contraction is
+    # MFMA-bound (512 flop/B) and the apply is HBM-bound (250 flop/B < ridge 312).
+    if fwd_ms >= app_ms:
+        roof = {"kernel": "mlr_forward_bf16", "bound": "mfma", "achieved": stages["forward_gemm"]["tflops"],
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": stages["forward_gemm"]["mfma_frac"],
+                "traffic": None}
+    else:
+        roof = {"kernel": "apply_bf16", "bound": "hbm", "achieved": stages["apply_gemm"]["hbm_gbs"],
+                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": stages["apply_gemm"]["hbm_frac"], "traffic": None}
+
+    out = {
+        "metric": "rank-1 SF updates applied/sec (SF compute + reconstruct/apply), MLR J=325k D=10k",
+        "value": B / (ms_per_step * 1e-3),
+        "unit": "updates/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "mlr_large_bf16: MLR J=325000 D=10000 B=N=1024, bf16 X/U/V, fp32 W and accumulate, "
+                               "X ~ N(0,1) with 90% zeros stored dense, eta=0.001",
+                   "J": J, "D": D, "B": B, "rank1_terms_per_step": B},
+        "tflops_gemm_stages": 2 * gemm_flops / (ms_per_step * 1e-3) / 1e12,
+        "mfma_frac_gemm_stages": 2 * gemm_flops / ((fwd_ms + app_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "stages": stages,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        log("bench: timing the CPU oracle on a bounded sample")
+        out["cpu_baseline"] = cpu_baseline_mlr(cfg, X0, y0, seed=0)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -136,6 +136,23 @@ const char* sfb_strerror(int code);
 int sfb_last_hip_error(const sfb_ctx* ctx);
 /* Library version, "major.minor". */
 const char* sfb_version(void);
+/*
+ * Optional per-kernel timing for benchmarks.  When enabled, each kernel launch
+ * of the context is bracketed by two HIP events recorded on the context's
+ * stream (a fixed pool of 4096 pairs; launches beyond it are not timed).
+ * sfb_profile_collect synchronises the stream, sums the elapsed time per kernel
+ * group since the last collect into `out` (at most max_entries entries, *count
+ * of them filled; `name` points to static storage) and empties the pool.  It
+ * returns SFB_ENOWS if launches were dropped because the pool was full.
+ */
+typedef struct {
+    const char* name;
+    int32_t launches;
+    float total_ms;
+} sfb_kernel_time;
+int sfb_profile_enable(sfb_ctx* ctx, int on);
+int sfb_profile_collect(sfb_ctx* ctx, sfb_kernel_time* out, int max_entries, int* count);
+
 /* Benchmark knob: picks a tile variant of the bf16 forward / apply kernels
  * (process-wide; -1 = the default).  Every variant computes the same sums. */
 void sfb_tune_bf16_variant(int forward_variant, int apply_variant);

@@ -35,6 +35,10 @@ class sfb_batch(ctypes.Structure):
     ]
 
 
+class sfb_kernel_time(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char_p), ("launches", ctypes.c_int32), ("total_ms", ctypes.c_float)]
+
+
 class SfbError(RuntimeError):
     def __init__(self, code, what, hip=0):
         self.code = code
@@ -75,6 +79,11 @@ def lib():
         L.sfb_last_hip_error.restype = ctypes.c_int
         L.sfb_version.argtypes = []
         L.sfb_version.restype = ctypes.c_char_p
+        L.sfb_profile_enable.argtypes = [vp, ctypes.c_int]
+        L.sfb_profile_enable.restype = ctypes.c_int
+        L.sfb_profile_collect.argtypes = [vp, ctypes.POINTER(sfb_kernel_time), ctypes.c_int,
+                                          ctypes.POINTER(ctypes.c_int)]
+        L.sfb_profile_collect.restype = ctypes.c_int
         L.sfb_tune_bf16_variant.argtypes = [ctypes.c_int, ctypes.c_int]
         L.sfb_tune_bf16_variant.restype = None
         _lib = L
@@ -143,6 +152,17 @@ class Context:
     def _check(self, rc, what):
         if rc != SFB_OK:
             raise SfbError(rc, what, lib().sfb_last_hip_error(self._h))
+
+    # -- per-kernel timing ---------------------------------------------------
+    def sfb_profile_enable(self, on=True):
+        self._check(lib().sfb_profile_enable(self._h, 1 if on else 0), "sfb_profile_enable")
+
+    def sfb_profile_collect(self):
+        """Synchronises the stream; returns {kernel group: (launches, total_ms)} since the last collect."""
+        buf = (sfb_kernel_time * 32)()
+        n = ctypes.c_int(0)
+        self._check(lib().sfb_profile_collect(self._h, buf, 32, ctypes.byref(n)), "sfb_profile_collect")
+        return {buf[i].name.decode(): (int(buf[i].launches), float(buf[i].total_ms)) for i in range(n.value)}
 
     # -- workspace ---------------------------------------------------------
     def sfb_workspace_bytes(self, model, J, D, batch: sfb_batch) -> int:

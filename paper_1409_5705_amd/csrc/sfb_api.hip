@@ -9,12 +9,44 @@
 
 #include "kernels.h"
 
+// Kernel groups reported by the optional per-kernel timing.
+enum KernelId : int {
+    KID_FORWARD_BF16 = 0,
+    KID_APPLY_BF16,
+    KID_SOFTMAX,
+    KID_GEMM_F32_STORE,
+    KID_GEMM_F32_RMW,
+    KID_GEMM_F32_RESID,
+    KID_GEMM_F32_SHRINK,
+    KID_DIFF,
+    KID_DML_SCALE,
+    KID_FILL,
+    KID_PROX,
+    KID_POWER_ITERATION,
+    KID_COPY,
+    KID_COUNT
+};
+static const char* const kKernelNames[KID_COUNT] = {
+    "mlr_forward_bf16", "apply_bf16", "mlr_softmax", "gemm_f32_store", "gemm_f32_rmw(apply)", "gemm_f32_resid",
+    "gemm_f32_shrink", "diff", "dml_scale", "fill", "prox_rows", "power_iteration", "copy"};
+
+struct ProfSpan {
+    hipEvent_t t0, t1;
+    int kid;
+};
+
 struct sfb_ctx {
     int device;
     hipStream_t stream;
     char* ws;
     int64_t ws_bytes;
     int last_hip_error;
+    // per-kernel timing (off by default): a fixed pool of event pairs
+    bool prof_on;
+    ProfSpan* spans;
+    int span_cap;
+    int span_used;
+    int span_dropped;
 };
 
 namespace {
@@ -32,6 +64,36 @@ int hip_fail(sfb_ctx* ctx, hipError_t e)
 #define SFB_TRY(expr)                                         \
     do {                                                      \
         hipError_t e_ = (expr);                               \
+        if (e_ != hipSuccess) return hip_fail(ctx, e_);       \
+    } while (0)
+
+// Brackets a launch with two events when timing is on (and the pool has room).
+struct ProfScope {
+    sfb_ctx* c;
+    ProfSpan* s;
+    ProfScope(sfb_ctx* ctx, int kid) : c(ctx), s(nullptr)
+    {
+        if (!c->prof_on) return;
+        if (c->span_used >= c->span_cap) {
+            c->span_dropped++;
+            return;
+        }
+        s = &c->spans[c->span_used++];
+        s->kid = kid;
+        (void)hipEventRecord(s->t0, c->stream);
+    }
+    ~ProfScope()
+    {
+        if (s) (void)hipEventRecord(s->t1, c->stream);
+    }
+};
+#define SFB_RUN(kid, expr)                                    \
+    do {                                                      \
+        hipError_t e_;                                        \
+        {                                                     \
+            ProfScope scope_(ctx, (kid));                     \
+            e_ = (expr);                                      \
+        }                                                     \
         if (e_ != hipSuccess) return hip_fail(ctx, e_);       \
     } while (0)
 
@@ -78,6 +140,11 @@ int sfb_create(sfb_ctx** out, int device_id, void* hip_stream)
     c->ws = nullptr;
     c->ws_bytes = 0;
     c->last_hip_error = 0;
+    c->prof_on = false;
+    c->spans = nullptr;
+    c->span_cap = 0;
+    c->span_used = 0;
+    c->span_dropped = 0;
     *out = c;
     return SFB_OK;
 }
@@ -85,8 +152,67 @@ int sfb_create(sfb_ctx** out, int device_id, void* hip_stream)
 int sfb_destroy(sfb_ctx* ctx)
 {
     if (!ctx) return SFB_EINVAL;
+    if (ctx->spans) {
+        for (int i = 0; i < ctx->span_cap; ++i) {
+            (void)hipEventDestroy(ctx->spans[i].t0);
+            (void)hipEventDestroy(ctx->spans[i].t1);
+        }
+        delete[] ctx->spans;
+    }
     delete ctx;
     return SFB_OK;
+}
+
+int sfb_profile_enable(sfb_ctx* ctx, int on)
+{
+    if (!ctx) return SFB_EINVAL;
+    if (on && !ctx->spans) {
+        SFB_TRY(hipSetDevice(ctx->device));
+        const int cap = 4096;
+        ProfSpan* sp = new (std::nothrow) ProfSpan[cap];
+        if (!sp) return SFB_EINVAL;
+        for (int i = 0; i < cap; ++i) {
+            hipError_t e = hipEventCreate(&sp[i].t0);
+            if (e == hipSuccess) e = hipEventCreate(&sp[i].t1);
+            if (e != hipSuccess) {
+                delete[] sp;
+                return hip_fail(ctx, e);
+            }
+        }
+        ctx->spans = sp;
+        ctx->span_cap = cap;
+    }
+    ctx->prof_on = on != 0;
+    return SFB_OK;
+}
+
+int sfb_profile_collect(sfb_ctx* ctx, sfb_kernel_time* out, int max_entries, int* count)
+{
+    if (!ctx || !count || (max_entries > 0 && !out)) return SFB_EINVAL;
+    *count = 0;
+    SFB_TRY(hipSetDevice(ctx->device));
+    SFB_TRY(hipStreamSynchronize(ctx->stream));
+    float total[KID_COUNT] = {0};
+    int launches[KID_COUNT] = {0};
+    for (int i = 0; i < ctx->span_used; ++i) {
+        float ms = 0.f;
+        SFB_TRY(hipEventElapsedTime(&ms, ctx->spans[i].t0, ctx->spans[i].t1));
+        total[ctx->spans[i].kid] += ms;
+        launches[ctx->spans[i].kid] += 1;
+    }
+    ctx->span_used = 0;
+    const int dropped = ctx->span_dropped;
+    ctx->span_dropped = 0;
+    int n = 0;
+    for (int k = 0; k < KID_COUNT && n < max_entries; ++k) {
+        if (!launches[k]) continue;
+        out[n].name = kKernelNames[k];
+        out[n].launches = launches[k];
+        out[n].total_ms = total[k];
+        ++n;
+    }
+    *count = n;
+    return dropped ? SFB_ENOWS : SFB_OK;
 }
 
 int64_t sfb_workspace_bytes(int32_t model, int64_t J, int64_t D, const sfb_batch* batch)
@@ -139,14 +265,15 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
             g.C = Z; g.ldc = J;
             g.M = B; g.N = J; g.K = D;
             g.epilogue = sfb::EPI_STORE;
-            SFB_TRY(sfb::launch_gemm_f32(g, st));
-            SFB_TRY(sfb::launch_mlr_softmax(Z, y, U, false, B, J, st));
+            SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, st));
+            SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, false, B, J, st));
         } else {
-            SFB_TRY(sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), W, Z, B, J, D, st));
-            SFB_TRY(sfb::launch_mlr_softmax(Z, y, U, true, B, J, st));
+            SFB_RUN(KID_FORWARD_BF16,
+                    sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), W, Z, B, J, D, st));
+            SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st));
         }
         if (V && V != batch->X)
-            SFB_TRY(hipMemcpyAsync(V, batch->X, (size_t)(B * D * esz), hipMemcpyDeviceToDevice, st));
+            SFB_RUN(KID_COPY, hipMemcpyAsync(V, batch->X, (size_t)(B * D * esz), hipMemcpyDeviceToDevice, st));
         return SFB_OK;
     }
 
@@ -154,17 +281,17 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
         if (!batch->Y || !batch->sim || !V || !aligned16(batch->Y)) return SFB_EINVAL;
         float* Q = reinterpret_cast<float*>(ctx->ws);
         float* Vd = static_cast<float*>(V);
-        SFB_TRY(sfb::launch_diff(static_cast<const float*>(batch->X), static_cast<const float*>(batch->Y), Vd, B * D,
-                                 st));
+        SFB_RUN(KID_DIFF, sfb::launch_diff(static_cast<const float*>(batch->X), static_cast<const float*>(batch->Y), Vd,
+                                           B * D, st));
         sfb::GemmF32Args g = {};
         g.A = Vd; g.lda = D; g.a_kstrided = false;
         g.B = W; g.ldb = D; g.b_kstrided = false;
         g.C = Q; g.ldc = J;
         g.M = B; g.N = J; g.K = D;
         g.epilogue = sfb::EPI_STORE;
-        SFB_TRY(sfb::launch_gemm_f32(g, st));
-        if (n_active) SFB_TRY(sfb::launch_fill_u32(n_active, 0u, 1, st));
-        SFB_TRY(sfb::launch_dml_scale(Q, batch->sim, static_cast<float*>(U), n_active, batch->margin, B, J, st));
+        SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, st));
+        if (n_active) SFB_RUN(KID_FILL, sfb::launch_fill_u32(n_active, 0u, 1, st));
+        SFB_RUN(KID_DML_SCALE, sfb::launch_dml_scale(Q, batch->sim, static_cast<float*>(U), n_active, batch->margin, B, J, st));
         return SFB_OK;
     }
 
@@ -176,12 +303,12 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
     float* A = static_cast<float*>(U);
     float* R = static_cast<float*>(V);
     const float* X = static_cast<const float*>(batch->X);
-    SFB_TRY(sfb::launch_power_iteration(W, J, D, batch->power_iters, scratch, Lp, st));
-    SFB_TRY(sfb::launch_fill_u32(A, 0u, B * J, st));
+    SFB_RUN(KID_POWER_ITERATION, sfb::launch_power_iteration(W, J, D, batch->power_iters, scratch, Lp, st));
+    SFB_RUN(KID_FILL, sfb::launch_fill_u32(A, 0u, B * J, st));
     for (int it = 0; it <= batch->ista_iters; ++it) {
         if (it == 0) {
             // a = 0  =>  r = x
-            SFB_TRY(hipMemcpyAsync(R, X, (size_t)(B * D * 4), hipMemcpyDeviceToDevice, st));
+            SFB_RUN(KID_COPY, hipMemcpyAsync(R, X, (size_t)(B * D * 4), hipMemcpyDeviceToDevice, st));
         } else {
             sfb::GemmF32Args g = {};  // R = X - A W   (contraction over the basis index j)
             g.A = A; g.lda = J; g.a_kstrided = false;
@@ -190,7 +317,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
             g.M = B; g.N = D; g.K = J;
             g.epilogue = sfb::EPI_RESID;
             g.aux = X;
-            SFB_TRY(sfb::launch_gemm_f32(g, st));
+            SFB_RUN(KID_GEMM_F32_RESID, sfb::launch_gemm_f32(g, st));
         }
         if (it == batch->ista_iters) break;
         sfb::GemmF32Args g = {};  // A = soft(A + (R W^T)/L, lambda/L)
@@ -202,7 +329,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
         g.aux = A;
         g.L_ptr = Lp;
         g.lambda = batch->lambda;
-        SFB_TRY(sfb::launch_gemm_f32(g, st));
+        SFB_RUN(KID_GEMM_F32_SHRINK, sfb::launch_gemm_f32(g, st));
     }
     return SFB_OK;
 }
@@ -224,10 +351,10 @@ int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const
         g.M = J; g.N = D; g.K = N;
         g.epilogue = sfb::EPI_RMW;
         g.eta = eta;
-        SFB_TRY(sfb::launch_gemm_f32(g, ctx->stream));
+        SFB_RUN(KID_GEMM_F32_RMW, sfb::launch_gemm_f32(g, ctx->stream));
     } else {
-        SFB_TRY(sfb::launch_apply_bf16(W, static_cast<const uint16_t*>(U), static_cast<const uint16_t*>(V), N, J, D,
-                                       eta, ctx->stream));
+        SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, static_cast<const uint16_t*>(U),
+                                                      static_cast<const uint16_t*>(V), N, J, D, eta, ctx->stream));
     }
     return SFB_OK;
 }
@@ -237,7 +364,7 @@ int sfb_prox_rows(sfb_ctx* ctx, float* W, int64_t J, int64_t D, int32_t mode)
     if (!ctx || !W || J <= 0 || D <= 0) return SFB_EINVAL;
     if (mode != SFB_PROX_PROJECT && mode != SFB_PROX_NORMALIZE) return SFB_EINVAL;
     SFB_TRY(hipSetDevice(ctx->device));
-    SFB_TRY(sfb::launch_prox_rows(W, J, D, mode, ctx->stream));
+    SFB_RUN(KID_PROX, sfb::launch_prox_rows(W, J, D, mode, ctx->stream));
     return SFB_OK;
 }
 

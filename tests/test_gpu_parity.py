@@ -238,7 +238,7 @@ def test_dml_sf(ctx, sfb, oracle, K, D, B, sigma):
     ctx.sfb_compute_sf(sfb.SFB_DML, dev(W0), dev(X), Y=dev(Y), sim=dev(sim), U=U, V=V, n_active=na, margin=1.0)
     Uo, Vo, no = oracle.dml_sf(W0, X, Y, sim, margin=1.0)
     d = np.sum(((X.astype(np.float64) - Y) @ W0.T.astype(np.float64)) ** 2, axis=1)
-    assert np.min(np.abs(d[sim < 0] - 1.0)) > 1e-4        # no pair sits at the kink, so the decision is unique
+    assert np.min(np.abs(d[sim < 0] - 1.0)) > 1e-5        # no pair within fp32 rounding of the kink: the decision is unique
     assert int(host(na)[0]) == no
     print("  n_active", no, "of", B)
     np.testing.assert_array_equal(host(V), (X - Y).astype(np.float32))
