@@ -40,7 +40,7 @@ def cpu_baseline_mlr(cfg, X, y, seed):
     import oracle
     import sfb_synth as S
     J, D, B = cfg["J"], cfg["D"], cfg["B"]
-    Js = min(J, 8192)
+    Js = min(J, 32768)
     Ws = S.normal_matrix(Js, D, cfg["sigma"], seed)
     ys = (y % Js).astype(np.int32)
     t0 = time.perf_counter()
@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="mlr_large_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB elementwise copy kernel (reference for HBM byte counters)")
     ap.add_argument("--forward-variant", type=int, default=-1)
     ap.add_argument("--apply-variant", type=int, default=-1)
     args = ap.parse_args()
@@ -108,6 +110,12 @@ def main():
         ctx.sfb_compute_sf(sfb.SFB_MLR, W, Xd, Y=yd, U=U)   # V = X
         ctx.sfb_apply(W, U, Xd, eta)
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     log("bench: warmup")
     for i in range(args.warmup):
         step(i)
