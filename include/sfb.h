@@ -72,9 +72,12 @@ int sfb_create(sfb_ctx** out, int device_id, void* hip_stream);
 int sfb_destroy(sfb_ctx* ctx);
 
 /* Bytes of device scratch sfb_compute_sf needs for this model/shape/batch
- * (0 is possible; negative sfb_status on bad arguments).  sfb_apply and
- * sfb_prox_rows need none. */
+ * (0 is possible; negative sfb_status on bad arguments). */
 int64_t sfb_workspace_bytes(int32_t model, int64_t J, int64_t D, const sfb_batch* batch);
+/* Bytes of device scratch sfb_apply needs (0 for fp32 factors; bf16 factors
+ * are transposed into it).  sfb_prox_rows needs none.  One workspace of the
+ * larger size serves both calls: its contents do not outlive a call. */
+int64_t sfb_apply_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dtype);
 
 /* Hands the context a caller-allocated device buffer (256-byte aligned) to use
  * as scratch until replaced.  The library never frees it.  Its contents are
@@ -117,7 +120,8 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
  * by rows, or one call per block: the results agree to rounding).  The
  * accumulation is fp32; each element of W is read and written exactly once by
  * exactly one workgroup, so the result is bit-reproducible.  eta may be
- * negative.  N == 0 is a no-op.  U and V are not modified.
+ * negative.  N == 0 is a no-op.  U and V are not modified.  Needs the workspace
+ * of sfb_apply_workspace_bytes (SFB_ENOWS otherwise).
  */
 int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const void* V,
               int64_t N, int32_t sf_dtype, float eta);

@@ -65,6 +65,8 @@ def lib():
         L.sfb_destroy.restype = ctypes.c_int
         L.sfb_workspace_bytes.argtypes = [i32, i64, i64, ctypes.POINTER(sfb_batch)]
         L.sfb_workspace_bytes.restype = i64
+        L.sfb_apply_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.sfb_apply_workspace_bytes.restype = i64
         L.sfb_set_workspace.argtypes = [vp, vp, i64]
         L.sfb_set_workspace.restype = ctypes.c_int
         L.sfb_compute_sf.argtypes = [vp, i32, vp, i64, i64, ctypes.POINTER(sfb_batch), vp, vp, vp]
@@ -180,6 +182,17 @@ class Context:
                         "sfb_set_workspace")
         self._ws = tensor
 
+    def sfb_apply_workspace_bytes(self, J, D, N, sf_dtype) -> int:
+        n = lib().sfb_apply_workspace_bytes(J, D, N, sf_dtype)
+        if n < 0:
+            raise SfbError(int(n), "sfb_apply_workspace_bytes")
+        return int(n)
+
+    def _grow_workspace(self, need):
+        have = 0 if self._ws is None else self._ws.numel()
+        if need > have:
+            self.sfb_set_workspace(torch.empty(need, dtype=torch.uint8, device=self.device))
+
     def _ensure_workspace(self, model, J, D, batch):
         need = self.sfb_workspace_bytes(model, J, D, batch)
         have = 0 if self._ws is None else self._ws.numel()
@@ -219,6 +232,7 @@ class Context:
         N = U.shape[0]
         if U.dtype != V.dtype:
             raise TypeError("U and V must share a dtype")
+        self._grow_workspace(self.sfb_apply_workspace_bytes(J, D, N, _dtype_code(U)))
         rc = lib().sfb_apply(self._h, _ptr(W, "W", dtype=torch.float32), J, D, _ptr(U, "U", shape=(N, J)),
                              _ptr(V, "V", shape=(N, D)), N, _dtype_code(U), float(eta))
         self._check(rc, "sfb_apply")

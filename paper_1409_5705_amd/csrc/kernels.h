@@ -44,8 +44,10 @@ hipError_t launch_gemm_f32(const GemmF32Args& a, hipStream_t stream);
 hipError_t launch_mlr_forward_bf16(const uint16_t* X, const float* W, float* Z,
                                    int64_t B, int64_t J, int64_t D, hipStream_t stream);
 // W[j][d] -= eta * sum_i U[i][j] * V[i][d];  U bf16 [N][J], V bf16 [N][D], W fp32 [J][D].
+// `workspace` (apply_bf16_workspace_bytes, 256-byte aligned) receives U^T and V^T.
+int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D);
 hipError_t launch_apply_bf16(float* W, const uint16_t* U, const uint16_t* V,
-                             int64_t N, int64_t J, int64_t D, float eta, hipStream_t stream);
+                             int64_t N, int64_t J, int64_t D, float eta, void* workspace, hipStream_t stream);
 // Selects a tile variant of the two kernels above (benchmark sweeps); -1 = default.
 void set_bf16_variant(int forward_variant, int apply_variant);
 

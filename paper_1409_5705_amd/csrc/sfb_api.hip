@@ -229,6 +229,14 @@ int64_t sfb_workspace_bytes(int32_t model, int64_t J, int64_t D, const sfb_batch
     }
 }
 
+int64_t sfb_apply_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dtype)
+{
+    if (J <= 0 || D <= 0 || N < 0 || !valid_dtype(sf_dtype)) return SFB_EINVAL;
+    if (sf_dtype == SFB_F32 || N == 0) return 0;
+    if (J % 8 != 0 || D % 8 != 0) return SFB_EINVAL;
+    return round_up(sfb::apply_bf16_workspace_bytes(N, J, D));
+}
+
 int sfb_set_workspace(sfb_ctx* ctx, void* dev_ptr, int64_t bytes)
 {
     if (!ctx || bytes < 0 || (bytes > 0 && !dev_ptr)) return SFB_EINVAL;
@@ -342,6 +350,8 @@ int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const
     if (N == 0) return SFB_OK;
     if (!U || !V || !aligned16(U) || !aligned16(V)) return SFB_EINVAL;
     if (sf_dtype == SFB_BF16 && (J % 8 != 0 || D % 8 != 0)) return SFB_EINVAL;
+    const int64_t need = sfb_apply_workspace_bytes(J, D, N, sf_dtype);
+    if (need > 0 && (!ctx->ws || ctx->ws_bytes < need)) return SFB_ENOWS;
     SFB_TRY(hipSetDevice(ctx->device));
     if (sf_dtype == SFB_F32) {
         sfb::GemmF32Args g = {};  // both factors are strided along the SF index
@@ -354,7 +364,7 @@ int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const
         SFB_RUN(KID_GEMM_F32_RMW, sfb::launch_gemm_f32(g, ctx->stream));
     } else {
         SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, static_cast<const uint16_t*>(U),
-                                                      static_cast<const uint16_t*>(V), N, J, D, eta, ctx->stream));
+                                                      static_cast<const uint16_t*>(V), N, J, D, eta, ctx->ws, ctx->stream));
     }
     return SFB_OK;
 }
