@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB elementwise copy kernel (reference for HBM byte counters)")
+    ap.add_argument("--no-shadow", action="store_true",
+                    help="do not attach a bf16 working copy of W (the forward then converts W on every call)")
     ap.add_argument("--forward-variant", type=int, default=-1)
     ap.add_argument("--apply-variant", type=int, default=-1)
     args = ap.parse_args()
@@ -104,6 +106,8 @@ def main():
         ys.append(torch.from_numpy(y).to(dev))
     U = torch.empty((B, J), dtype=torch.bfloat16, device=dev)
     ctx = sfb.Context(0)
+    if not args.no_shadow:
+        ctx.sfb_shadow_attach(W)     # bf16 working copy of W, kept current by sfb_apply (setup, like W itself)
 
     def step(i):
         Xd, yd = Xs[i % len(Xs)], ys[i % len(ys)]
@@ -136,13 +140,17 @@ def main():
 
     # per-kernel averages from the HIP events recorded on the library's stream
     kt = {k: v[1] / v[0] for k, v in prof.items()}          # ms per launch
+    if "shadow_convert" in kt:                                # no working copy attached: conversion is part of forward
+        kt["mlr_forward_bf16"] += kt["shadow_convert"]
     fwd_ms = kt.get("mlr_forward_bf16", float("nan"))
     app_ms = kt.get("apply_bf16", float("nan"))
     smx_ms = kt.get("mlr_softmax", float("nan"))
     gemm_flops = 2.0 * B * J * D                             # per GEMM stage
-    # algorithmic HBM bytes per launch
-    fwd_bytes = J * D * 4 + B * D * 2 + B * J * 4            # W read once, X, logits written
-    app_bytes = 2 * J * D * 4 + B * J * 2 + B * D * 2        # W read + written once, U, V
+    # algorithmic HBM bytes per launch (the bf16 working copy of W counts: read by forward, written by apply)
+    wb = 2 if not args.no_shadow else 4
+    fwd_bytes = J * D * wb + B * D * 2 + B * J * 4           # W (copy) read once, X, logits written
+    app_bytes = 2 * J * D * 4 + (J * D * 2 if not args.no_shadow else 0) + B * J * 2 + B * D * 2
+    # ^ W read + written once, bf16 copy written, U, V
     smx_bytes = B * J * 4 + B * J * 2                        # logits read once, U written
     stages = {
         "forward_gemm": {"ms": fwd_ms, "tflops": gemm_flops / fwd_ms / 1e9,

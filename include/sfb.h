@@ -79,6 +79,25 @@ int64_t sfb_workspace_bytes(int32_t model, int64_t J, int64_t D, const sfb_batch
  * larger size serves both calls: its contents do not outlive a call. */
 int64_t sfb_apply_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dtype);
 
+/*
+ * Optional bf16 working copy ("shadow") of one parameter matrix, for the bf16
+ * multiclass-logistic path: fp32 master weights W plus a bf16 copy with
+ * 128-byte-aligned rows that the forward contraction reads instead of W (half
+ * the bytes, every request a whole cache line).  sfb_shadow_attach converts W
+ * into the caller-allocated buffer (sfb_shadow_bytes, 256-byte aligned; the
+ * library never frees it) and remembers (W, J, D).  While attached,
+ *   - sfb_compute_sf(SFB_MLR, bf16) on that W reads the copy and needs
+ *     sfb_shadow_bytes less workspace;
+ *   - sfb_apply and sfb_prox_rows on that W keep the copy current;
+ *   - any other modification of W by the caller must be followed by another
+ *     sfb_shadow_attach (a refresh), otherwise the copy is stale.
+ * Without an attached copy the bf16 path converts W into the workspace on every
+ * sfb_compute_sf call: same results, one more pass over W.
+ */
+int64_t sfb_shadow_bytes(int64_t J, int64_t D);
+int sfb_shadow_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* dev_ptr, int64_t bytes);
+int sfb_shadow_detach(sfb_ctx* ctx);
+
 /* Hands the context a caller-allocated device buffer (256-byte aligned) to use
  * as scratch until replaced.  The library never frees it.  Its contents are
  * undefined after any call. */

@@ -67,6 +67,12 @@ def lib():
         L.sfb_workspace_bytes.restype = i64
         L.sfb_apply_workspace_bytes.argtypes = [i64, i64, i64, i32]
         L.sfb_apply_workspace_bytes.restype = i64
+        L.sfb_shadow_bytes.argtypes = [i64, i64]
+        L.sfb_shadow_bytes.restype = i64
+        L.sfb_shadow_attach.argtypes = [vp, vp, i64, i64, vp, i64]
+        L.sfb_shadow_attach.restype = ctypes.c_int
+        L.sfb_shadow_detach.argtypes = [vp]
+        L.sfb_shadow_detach.restype = ctypes.c_int
         L.sfb_set_workspace.argtypes = [vp, vp, i64]
         L.sfb_set_workspace.restype = ctypes.c_int
         L.sfb_compute_sf.argtypes = [vp, i32, vp, i64, i64, ctypes.POINTER(sfb_batch), vp, vp, vp]
@@ -139,6 +145,24 @@ class Context:
         if rc != SFB_OK:
             raise SfbError(rc, "sfb_create")
         self._ws = None
+        self._shadow = None          # (W tensor, buffer tensor)
+
+    # -- bf16 working copy of W ----------------------------------------------
+    def sfb_shadow_attach(self, W):
+        """Allocates (once) and fills the bf16 working copy of W; call again to refresh it."""
+        J, D = W.shape
+        need = lib().sfb_shadow_bytes(J, D)
+        if need < 0:
+            raise SfbError(int(need), "sfb_shadow_bytes")
+        buf = self._shadow[1] if self._shadow is not None and self._shadow[1].numel() >= need else \
+            torch.empty(need, dtype=torch.uint8, device=self.device)
+        self._check(lib().sfb_shadow_attach(self._h, _ptr(W, "W", dtype=torch.float32), J, D, buf.data_ptr(),
+                                            buf.numel()), "sfb_shadow_attach")
+        self._shadow = (W, buf)
+
+    def sfb_shadow_detach(self):
+        self._check(lib().sfb_shadow_detach(self._h), "sfb_shadow_detach")
+        self._shadow = None
 
     def close(self):
         if self._h:
@@ -193,8 +217,11 @@ class Context:
         if need > have:
             self.sfb_set_workspace(torch.empty(need, dtype=torch.uint8, device=self.device))
 
-    def _ensure_workspace(self, model, J, D, batch):
+    def _ensure_workspace(self, model, J, D, batch, W=None):
         need = self.sfb_workspace_bytes(model, J, D, batch)
+        if (model == SFB_MLR and batch.in_dtype == SFB_BF16 and self._shadow is not None and W is not None
+                and self._shadow[0].data_ptr() == W.data_ptr() and tuple(self._shadow[0].shape) == (J, D)):
+            need -= lib().sfb_shadow_bytes(J, D)
         have = 0 if self._ws is None else self._ws.numel()
         if need > have:
             self.sfb_set_workspace(torch.empty(need, dtype=torch.uint8, device=self.device))
@@ -219,7 +246,7 @@ class Context:
         elif model == SFB_DML:
             b.Y = _ptr(Y, "Y", dtype=X.dtype, shape=(B, D))
             b.sim = _ptr(sim, "sim", dtype=torch.int8, shape=(B,))
-        self._ensure_workspace(model, J, D, b)
+        self._ensure_workspace(model, J, D, b, W)
         rc = lib().sfb_compute_sf(self._h, model, _ptr(W, "W", dtype=torch.float32), J, D, ctypes.byref(b),
                                   _ptr(U, "U", shape=(B, J)),
                                   _ptr(V, "V", shape=(B, D)) if V is not None else None,

@@ -38,17 +38,23 @@ struct GemmF32Args {
 hipError_t launch_gemm_f32(const GemmF32Args& a, hipStream_t stream);
 
 // ---------------------------------------------------------------------------
-// bf16 MFMA kernels of the large MLR path (fp32 accumulate).
+// bf16 MFMA kernel of the large MLR path (fp32 accumulate) and its layout helpers.
 // ---------------------------------------------------------------------------
-// Z[b][j] = sum_d X[b][d] * bf16(W[j][d]);  X bf16 [B][D], W fp32 [J][D], Z fp32 [B][J].
-hipError_t launch_mlr_forward_bf16(const uint16_t* X, const float* W, float* Z,
+// Row pitch (elements) of the aligned bf16 operands: cols rounded up to 64.
+int64_t bf16_pitch(int64_t cols);
+// shadow[j][0..pitch) = bf16(W[j][0..D)), zero padded; pitch = bf16_pitch(D).
+hipError_t launch_shadow_from_w(const float* W, uint16_t* shadow, int64_t J, int64_t D, hipStream_t stream);
+// Z[b][j] = sum_d X[b][d] * shadow[j][d];  X bf16 [B][D], Z fp32 [B][J].
+// X_aligned: scratch for the aligned copy of X, B * bf16_pitch(D) elements.
+hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, float* Z, uint16_t* X_aligned,
                                    int64_t B, int64_t J, int64_t D, hipStream_t stream);
 // W[j][d] -= eta * sum_i U[i][j] * V[i][d];  U bf16 [N][J], V bf16 [N][D], W fp32 [J][D].
 // `workspace` (apply_bf16_workspace_bytes, 256-byte aligned) receives U^T and V^T.
+// W_shadow (nullable): bf16 copy of W, refreshed with the new values.
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D);
-hipError_t launch_apply_bf16(float* W, const uint16_t* U, const uint16_t* V,
-                             int64_t N, int64_t J, int64_t D, float eta, void* workspace, hipStream_t stream);
-// Selects a tile variant of the two kernels above (benchmark sweeps); -1 = default.
+hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, const uint16_t* U, const uint16_t* V, int64_t N,
+                             int64_t J, int64_t D, float eta, void* workspace, hipStream_t stream);
+// Timing experiments (benchmark sweeps): variant / 100 = debug bits; -1 = normal.
 void set_bf16_variant(int forward_variant, int apply_variant);
 
 // ---------------------------------------------------------------------------

@@ -24,11 +24,12 @@ enum KernelId : int {
     KID_PROX,
     KID_POWER_ITERATION,
     KID_COPY,
+    KID_SHADOW,
     KID_COUNT
 };
 static const char* const kKernelNames[KID_COUNT] = {
     "mlr_forward_bf16", "apply_bf16", "mlr_softmax", "gemm_f32_store", "gemm_f32_rmw(apply)", "gemm_f32_resid",
-    "gemm_f32_shrink", "diff", "dml_scale", "fill", "prox_rows", "power_iteration", "copy"};
+    "gemm_f32_shrink", "diff", "dml_scale", "fill", "prox_rows", "power_iteration", "copy", "shadow_convert"};
 
 struct ProfSpan {
     hipEvent_t t0, t1;
@@ -47,6 +48,10 @@ struct sfb_ctx {
     int span_cap;
     int span_used;
     int span_dropped;
+    // bf16 working copy of one parameter matrix (sfb_shadow_attach)
+    const float* shadow_W;
+    uint16_t* shadow_buf;
+    int64_t shadow_J, shadow_D;
 };
 
 namespace {
@@ -145,6 +150,9 @@ int sfb_create(sfb_ctx** out, int device_id, void* hip_stream)
     c->span_cap = 0;
     c->span_used = 0;
     c->span_dropped = 0;
+    c->shadow_W = nullptr;
+    c->shadow_buf = nullptr;
+    c->shadow_J = c->shadow_D = 0;
     *out = c;
     return SFB_OK;
 }
@@ -222,11 +230,45 @@ int64_t sfb_workspace_bytes(int32_t model, int64_t J, int64_t D, const sfb_batch
     const int64_t B = batch->B;
     switch (model) {
         case SFB_MLR:
+            if (batch->in_dtype == SFB_BF16)   // logits, aligned copy of X, bf16 copy of W
+                return round_up(B * J * 4) + round_up(B * sfb::bf16_pitch(D) * 2) + sfb_shadow_bytes(J, D);
+            return round_up(B * J * 4);
         case SFB_DML:
-            return round_up(B * J * 4);  // logits Z[B][J] / projections Q[B][K], fp32
+            return round_up(B * J * 4);  // projections Q[B][K], fp32
         default:
             return sc_layout(J, D).total;
     }
+}
+
+int64_t sfb_shadow_bytes(int64_t J, int64_t D)
+{
+    if (J <= 0 || D <= 0 || D % 8 != 0) return SFB_EINVAL;
+    return round_up(J * sfb::bf16_pitch(D) * 2);
+}
+
+int sfb_shadow_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* dev_ptr, int64_t bytes)
+{
+    if (!ctx || !W || !dev_ptr || !aligned16(W)) return SFB_EINVAL;
+    const int64_t need = sfb_shadow_bytes(J, D);
+    if (need < 0) return SFB_EINVAL;
+    if (bytes < need) return SFB_ENOWS;
+    if (reinterpret_cast<uintptr_t>(dev_ptr) % ALIGN != 0) return SFB_EINVAL;
+    SFB_TRY(hipSetDevice(ctx->device));
+    SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, static_cast<uint16_t*>(dev_ptr), J, D, ctx->stream));
+    ctx->shadow_W = W;
+    ctx->shadow_buf = static_cast<uint16_t*>(dev_ptr);
+    ctx->shadow_J = J;
+    ctx->shadow_D = D;
+    return SFB_OK;
+}
+
+int sfb_shadow_detach(sfb_ctx* ctx)
+{
+    if (!ctx) return SFB_EINVAL;
+    ctx->shadow_W = nullptr;
+    ctx->shadow_buf = nullptr;
+    ctx->shadow_J = ctx->shadow_D = 0;
+    return SFB_OK;
 }
 
 int64_t sfb_apply_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dtype)
@@ -256,7 +298,9 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
     if (!W || !aligned16(W)) return SFB_EINVAL;
     if (B == 0) return SFB_OK;
     if (!batch->X || !U || !aligned16(batch->X) || !aligned16(U) || (V && !aligned16(V))) return SFB_EINVAL;
-    const int64_t need = sfb_workspace_bytes(model, J, D, batch);
+    const bool has_shadow = ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D;
+    int64_t need = sfb_workspace_bytes(model, J, D, batch);
+    if (model == SFB_MLR && batch->in_dtype == SFB_BF16 && has_shadow) need -= sfb_shadow_bytes(J, D);
     if (need > 0 && (!ctx->ws || ctx->ws_bytes < need)) return SFB_ENOWS;
     SFB_TRY(hipSetDevice(ctx->device));
     hipStream_t st = ctx->stream;
@@ -276,8 +320,15 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
             SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, st));
             SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, false, B, J, st));
         } else {
+            uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + round_up(B * J * 4));
+            const uint16_t* Wb = ctx->shadow_buf;
+            if (!has_shadow) {   // no working copy attached: make one for this call
+                uint16_t* tmp = Xa + round_up(B * sfb::bf16_pitch(D) * 2) / 2;
+                SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, tmp, J, D, st));
+                Wb = tmp;
+            }
             SFB_RUN(KID_FORWARD_BF16,
-                    sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), W, Z, B, J, D, st));
+                    sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), Wb, Z, Xa, B, J, D, st));
             SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st));
         }
         if (V && V != batch->X)
@@ -362,9 +413,15 @@ int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const
         g.epilogue = sfb::EPI_RMW;
         g.eta = eta;
         SFB_RUN(KID_GEMM_F32_RMW, sfb::launch_gemm_f32(g, ctx->stream));
+        if (ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D)
+            SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, ctx->shadow_buf, J, D, ctx->stream));
     } else {
-        SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, static_cast<const uint16_t*>(U),
-                                                      static_cast<const uint16_t*>(V), N, J, D, eta, ctx->ws, ctx->stream));
+        uint16_t* Wb = (ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D)
+                           ? ctx->shadow_buf
+                           : nullptr;
+        SFB_RUN(KID_APPLY_BF16,
+                sfb::launch_apply_bf16(W, Wb, static_cast<const uint16_t*>(U), static_cast<const uint16_t*>(V), N, J, D,
+                                       eta, ctx->ws, ctx->stream));
     }
     return SFB_OK;
 }
@@ -375,6 +432,8 @@ int sfb_prox_rows(sfb_ctx* ctx, float* W, int64_t J, int64_t D, int32_t mode)
     if (mode != SFB_PROX_PROJECT && mode != SFB_PROX_NORMALIZE) return SFB_EINVAL;
     SFB_TRY(hipSetDevice(ctx->device));
     SFB_RUN(KID_PROX, sfb::launch_prox_rows(W, J, D, mode, ctx->stream));
+    if (ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D)
+        SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, ctx->shadow_buf, J, D, ctx->stream));
     return SFB_OK;
 }
 

@@ -55,6 +55,12 @@ def test_workspace_bytes_logic(sfb):
     wb = lambda model, J, D, b: L.sfb_workspace_bytes(model, J, D, ctypes.byref(b))
     assert wb(sfb.SFB_MLR, 100, 64, _batch(sfb, B=8)) >= 8 * 100 * 4
     assert wb(sfb.SFB_MLR, 100, 64, _batch(sfb, B=8)) % 256 == 0
+    # bf16 MLR: logits + aligned copy of X + room for a bf16 copy of W
+    full = wb(sfb.SFB_MLR, 104, 72, _batch(sfb, B=8, in_dtype=1, sf_dtype=1))
+    assert full >= 8 * 104 * 4 + 8 * 128 * 2 + L.sfb_shadow_bytes(104, 72)
+    assert L.sfb_shadow_bytes(104, 72) >= 104 * 128 * 2 and L.sfb_shadow_bytes(104, 70) == sfb.SFB_EINVAL
+    assert L.sfb_apply_workspace_bytes(104, 72, 10, 1) >= (104 + 72) * 64 * 2
+    assert L.sfb_apply_workspace_bytes(104, 72, 10, 0) == 0
     assert wb(sfb.SFB_DML, 16, 64, _batch(sfb, B=4)) >= 4 * 16 * 4
     assert wb(sfb.SFB_SC, 128, 64, _batch(sfb)) > (64 + 128 + 64) * 4
     # bad arguments are reported, not crashed on

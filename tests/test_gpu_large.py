@@ -40,6 +40,7 @@ def big(sfb):
     Xd = torch.from_numpy(S.bf16_bits(X)).to("cuda:0").view(torch.bfloat16)
     yd = torch.from_numpy(y).to("cuda:0")
     ctx = sfb.Context(0)
+    ctx.sfb_shadow_attach(W)      # the configuration the bench times
     yield dict(W=W, X=X, y=y, Xd=Xd, yd=yd, ctx=ctx, J=J, D=D, B=B)
     ctx.close()
 

@@ -211,6 +211,37 @@ def test_apply_bf16(ctx, sfb, oracle, N, J, D):
     _trajectory_check(host(W), ref, W0, 1, TOL_F32)
 
 
+def test_bf16_shadow_stays_current(sfb, oracle):
+    """With a bf16 working copy of W attached, SFs after several applies (and a prox) equal those of a
+    context that converts W afresh on every call, bit for bit."""
+    J, D, B, eta = 520, 328, 200, 0.05
+    W0 = S.normal_matrix(J, D, 0.05, seed=21)
+    ca, cb = sfb.Context(0), sfb.Context(0)
+    Wa, Wb = dev(W0), dev(W0)
+    ca.sfb_shadow_attach(Wa)
+    Ua = torch.empty((B, J), dtype=torch.bfloat16, device="cuda:0"); Ub = torch.empty_like(Ua)
+    for step in range(3):
+        X, y = S.mlr_batch(J, D, B, seed=21, step=step, zero_frac=0.5, bf16=True)
+        Xd, yd = dev_bf16(X), dev(y)
+        ca.sfb_compute_sf(sfb.SFB_MLR, Wa, Xd, Y=yd, U=Ua)
+        cb.sfb_compute_sf(sfb.SFB_MLR, Wb, Xd, Y=yd, U=Ub)
+        assert torch.equal(Ua, Ub), step
+        if step == 2:
+            Uo, _ = oracle.mlr_sf(host(Wb), X, y)
+            assert rel_err(host(Ua), Uo) <= TOL_BF16
+        ca.sfb_apply(Wa, Ua, Xd, eta); cb.sfb_apply(Wb, Ub, Xd, eta)
+        assert torch.equal(Wa, Wb)
+        if step == 1:
+            ca.sfb_prox_rows(Wa, sfb.SFB_PROX_PROJECT); cb.sfb_prox_rows(Wb, sfb.SFB_PROX_PROJECT)
+    # a caller-side change of W must be followed by a refresh
+    Wa.mul_(0.5); Wb.mul_(0.5)
+    ca.sfb_shadow_attach(Wa)
+    ca.sfb_compute_sf(sfb.SFB_MLR, Wa, Xd, Y=yd, U=Ua)
+    cb.sfb_compute_sf(sfb.SFB_MLR, Wb, Xd, Y=yd, U=Ub)
+    assert torch.equal(Ua, Ub)
+    ca.close(); cb.close()
+
+
 def test_bf16_rejects_unaligned_shapes(ctx, sfb):
     W = torch.zeros((12, 16), dtype=torch.float32, device="cuda:0")       # J % 8 != 0
     U = torch.zeros((4, 12), dtype=torch.bfloat16, device="cuda:0")
