@@ -80,7 +80,7 @@ struct Params {
     int tiles_m, tiles_n;
     int64_t tiles_total;
     int group_m;        // raster: groups of group_m row-tiles, row-tile index fastest inside a group
-    int dbg;            // timing experiments: 2 = skip epilogue, 4 = skip MFMA
+    int dbg;            // timing experiments: 2 = skip epilogue, 4 = skip MFMA, 8 = no shadow store
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
@@ -232,23 +232,6 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_SIMD) void sf_gemm_kernel(Param
         int64_t con_k = 0, con_tile = 0, cur_m0 = 0, cur_n0 = 0;
         tile_origin(0, cur_m0, cur_n0);
 
-        // Apply: during the last steps of a tile's k-loop the consumers touch the
-        // lines of the W tile (one dword per 128-byte line, value discarded) so the
-        // epilogue's loads find them in L2.  Their vector-memory counter is idle in
-        // the k-loop.  The loads are inline asm writing one never-read register
-        // that stays live to the end: the compiler's own vmcnt waits can only get
-        // stricter by them.
-        uint32_t pf_sink = 0;
-        constexpr int PF_STEPS = BM * (BN / 32) / (NCONS * 64);   // lines of the C tile / lines touched a step
-        auto prefetch_c = [&](int step) {
-            const int u = (step * NCONS + wave) * 64 + lane;
-            int row = u / (BN / 32), line = u % (BN / 32);
-            if (cur_m0 + row >= p.M) row = 0;
-            if (cur_n0 + line * 32 >= p.N) line = 0;
-            const char* addr = reinterpret_cast<const char*>(p.C) + ((cur_m0 + row) * p.ldc + cur_n0 + line * 32) * 4;
-            asm volatile("global_load_dword %0, %1, off" : "+v"(pf_sink) : "v"(addr) : "memory");
-        };
-
         // LDS read offsets of this lane: chunk g of rows wm0 + l32 (+32) of the A
         // tile and wn0 + l32 (+32) of the B tile, in the stage being consumed.
         const char* const lds_bytes = reinterpret_cast<const char*>(lds);
@@ -281,46 +264,79 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_SIMD) void sf_gemm_kernel(Param
         };
 
         // Epilogue of one tile.  Register i of lane (g, l32) of a 32x32 MFMA tile
-        // is row 8*(i/4) + 4*g + i%4, column l32: a wavefront access covers two
-        // 128-byte row segments of C.  Addresses are a uniform base plus one
-        // 32-bit per-lane offset (the host checks that a tile of C spans < 2 GiB).
-        const uint32_t lane_off_c = (uint32_t)(((wm0 + 4 * g) * p.ldc + wn0 + l32) * 4);
-        const uint32_t lane_off_s = (uint32_t)(((wm0 + 4 * g) * p.ld_shadow + wn0 + l32) * 2);
+        // is row 8*(i/4) + 4*g + i%4, column l32.  Two column-adjacent tiles are
+        // first combined with v_permlane32_swap (upper half of one register <->
+        // lower half of the other): afterwards one register holds ONE row across
+        // 64 consecutive columns (lane = column), the other the row 4 below.  Every
+        // access of C is then 256 contiguous bytes (128 for the bf16 copy) at a
+        // uniform row address plus a per-lane column offset.
+        static_assert(TN % 2 == 0, "tiles are paired along n");
+        // C is addressed through a raw buffer descriptor based at this wave's corner
+        // of the tile: row offsets are scalar, the column offset is one register per
+        // lane, so no per-row address registers are live while loads are in flight.
+        auto make_rsrc = [&](const void* base) {
+            const uint64_t a = reinterpret_cast<uint64_t>(base);
+            // (the builtin returns a signed int: narrow to 32 unsigned bits before widening)
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+            const uint64_t u = ((uint64_t)hi << 32) | (uint64_t)lo;
+            return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(u), 0, 0xffffffff, 0x00020000);
+        };
         auto epilogue_tile = [&](int64_t m0, int64_t n0, auto guard_tag) {
             constexpr bool GUARD = decltype(guard_tag)::value;
-            char* const cb = reinterpret_cast<char*>(p.C + m0 * p.ldc + n0);
-            char* const sb = p.shadow ? reinterpret_cast<char*>(p.shadow + m0 * p.ld_shadow + n0) : nullptr;
+            const auto crs = make_rsrc(p.C + (m0 + wm0) * p.ldc + n0 + wn0);
+            const bool has_shadow = p.shadow && !(p.dbg & 8);
+            const auto srs = make_rsrc(has_shadow ? p.shadow + (m0 + wm0) * p.ld_shadow + n0 + wn0 : p.shadow);
+            const int64_t rows_left = p.M - (m0 + wm0);
+            const uint32_t row_c = (uint32_t)p.ldc * 4u, row_s = (uint32_t)p.ld_shadow * 2u;
+            // One block = 32 rows x 64 columns (two column-adjacent MFMA tiles).  The loads of
+            // block q+1 are in flight while block q is combined and stored.
+            constexpr int NQ = TM * (TN / 2);
+            float w[2][32];
+            auto load_block = [&](int q, float* dst) {
+                const int ta = q / (TN / 2), tp = q % (TN / 2);
+                const bool col_ok = !GUARD || (n0 + wn0 + tp * 64 + lane < p.N);
+                const uint32_t coff = (uint32_t)(tp * 64 + lane);
 #pragma unroll
-            for (int t = 0; t < TM * TN; ++t) {
-                const int ta = t / TN, tb = t % TN;
-                const int64_t row0 = m0 + wm0 + 4 * g + ta * 32, col = n0 + wn0 + tb * 32 + l32;
-                auto inside = [&](int dr) { return !GUARD || (row0 + dr < p.M && col < p.N); };
-                auto caddr = [&](int dr) {
-                    return reinterpret_cast<float*>(cb + (((int64_t)(ta * 32 + dr) * p.ldc + tb * 32) * 4) + lane_off_c);
-                };
-                if (MODE == MODE_FWD) {
+                for (int e = 0; e < 32; ++e) {
+                    const int i = e / 2, dr = ta * 32 + 8 * (i / 4) + (i % 4) + 4 * (e & 1);
+                    dst[e] = 0.f;
+                    if (col_ok && (!GUARD || dr < rows_left))
+                        dst[e] = __uint_as_float(
+                            __builtin_amdgcn_raw_buffer_load_b32(crs, coff * 4u, (uint32_t)dr * row_c, 0));
+                }
+            };
+            if (MODE == MODE_APPLY) load_block(0, w[0]);
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int dr = 8 * (i / 4) + (i % 4);
-                        if (inside(dr)) *caddr(dr) = acc[ta][tb][i];
-                    }
-                } else {
-                    float wv[16];
+            for (int q = 0; q < NQ; ++q) {
+                const int ta = q / (TN / 2), tp = q % (TN / 2);
+                if (MODE == MODE_APPLY && q + 1 < NQ) load_block(q + 1, w[(q + 1) & 1]);
+                const bool col_ok = !GUARD || (n0 + wn0 + tp * 64 + lane < p.N);
+                const uint32_t coff = (uint32_t)(tp * 64 + lane);
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int dr = 8 * (i / 4) + (i % 4);
-                        wv[i] = 0.f;
-                        if (inside(dr)) wv[i] = *caddr(dr);
-                    }
+                for (int i = 0; i < 16; ++i) {
+                    // (element first into a scalar: bit-casting a vector element directly is
+                    // miscompiled by this toolchain)
+                    const float lo = acc[ta][2 * tp][i], hi = acc[ta][2 * tp + 1][i];
+                    const auto sw =
+                        __builtin_amdgcn_permlane32_swap(__float_as_uint(lo), __float_as_uint(hi), false, false);
+                    const uint32_t s0 = sw[0], s1 = sw[1];
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int dr = 8 * (i / 4) + (i % 4);
-                        const float w = wv[i] - p.eta * acc[ta][tb][i];
-                        if (inside(dr)) {
-                            *caddr(dr) = w;
-                            if (sb)
-                                *reinterpret_cast<uint16_t*>(sb + (((int64_t)(ta * 32 + dr) * p.ld_shadow + tb * 32) * 2) +
-                                                             lane_off_s) = (uint16_t)(pack_bf16(w, 0.f) & 0xffffu);
+                    for (int half = 0; half < 2; ++half) {
+                        const float val = __uint_as_float(half ? s1 : s0);
+                        const int dr = ta * 32 + 8 * (i / 4) + (i % 4) + 4 * half;
+                        if (col_ok && (!GUARD || dr < rows_left)) {
+                            if (MODE == MODE_FWD) {
+                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), crs, coff * 4u,
+                                                                      (uint32_t)dr * row_c, 0);
+                            } else {
+                                const float nw = w[q & 1][2 * i + half] - p.eta * val;
+                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(nw), crs, coff * 4u,
+                                                                      (uint32_t)dr * row_c, 0);
+                                if (has_shadow)
+                                    __builtin_amdgcn_raw_buffer_store_b16((uint16_t)(pack_bf16(nw, 0.f) & 0xffffu),
+                                                                          srs, coff * 2u, (uint32_t)dr * row_s, 0);
+                            }
                         }
                     }
                 }
@@ -334,8 +350,6 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_SIMD) void sf_gemm_kernel(Param
         };
 
         auto consume = [&](int64_t s) {
-            if (MODE == MODE_APPLY && nk >= PF_STEPS && con_k >= nk - PF_STEPS)
-                prefetch_c((int)(con_k - (nk - PF_STEPS)));
             if (!(p.dbg & 4)) mfma_slice();
             flip_stage();
             if (++con_k == nk) {
@@ -358,8 +372,6 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_SIMD) void sf_gemm_kernel(Param
             if (s + 1 < S) consume(s + 1);
             __syncthreads();
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        asm volatile("" ::"v"(pf_sink));
     }
 }
 
