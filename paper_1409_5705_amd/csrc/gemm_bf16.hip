@@ -14,26 +14,34 @@
 //            (the only pass over W), which also refreshes the shadow.
 //
 // What the measurements on MI355X dictated:
-//   * A wavefront issues at most one instruction every four cycles and the
-//     vector-memory path of a CU sustains ~110 outstanding 128-byte requests, so
-//     the kernel is bound by requests per flop and by instructions per slice,
-//     not by MFMA rate: hence large tiles, aligned bf16 operands only (every
-//     request is a whole line), and a loader that runs nothing but loads, a
-//     handful of address operations and LDS writes per k-slice.
-//   * One-slice-deep prefetch left the MFMA pipe idle behind ~3 us tail
-//     latencies: the kernel is persistent and warp-specialised, 512 threads =
-//     4 consumer wavefronts (MFMA + epilogue, 128 x 64 or 64 x 128 each) + 4
-//     producer wavefronts that keep the loads of two k-slices in flight in
-//     registers and run ahead across tile boundaries, so an epilogue overlaps
-//     the next tile's loads.  One workgroup barrier per k-slice, LDS
-//     double-buffered.  (256 x 256 tiles with 8 consumer wavefronts would halve
-//     the requests per flop again but do not fit the 168 registers a wavefront
-//     gets at three per SIMD without spilling.)
+//   * The vector-memory path of a CU sustains ~110 outstanding 128-byte requests
+//     and a wavefront issues at most one instruction every four cycles, so the
+//     kernel is bound by requests and instructions per flop, not by MFMA rate.
+//     Hence the largest tile the register file holds, 256 x 256 per workgroup of
+//     four wavefronts (one per SIMD, 128 x 128 = 256 accumulator registers
+//     each), aligned bf16 operands only (every request is a whole line), and
+//     operand tiles that go from global memory straight into LDS
+//     (global_load_lds_dwordx4: no staging registers, no LDS write
+//     instructions, 16 load instructions per wavefront and k-slice).
 //   * LDS rows are 128 bytes, the eight 16-byte chunks of a row XOR-swizzled by
-//     a function of the row: conflict-free operand reads, no padding.
-//   * Workgroup ids are dealt round-robin to the 8 XCDs (one L2 each): the 32
-//     workgroups of an XCD walk 32 consecutive tiles of a raster in which tiles
-//     sharing operand panels are neighbours.
+//     a function of the row: conflict-free operand reads, no padding.  A direct
+//     load writes 64 lanes x 16 bytes = 8 consecutive LDS rows; the swizzle is
+//     applied on the global side (each lane fetches the chunk that belongs in
+//     its slot).
+//   * Two LDS stages of 64 KiB.  The loads of slice s+2 are issued as soon as
+//     every wavefront has read the last fragments of slice s, spread over the
+//     last two k-steps of the slice (one load per two MFMAs: a burst of loads
+//     blocks the wavefront in the memory-issue stage while the MFMA pipe runs
+//     dry), and have one whole slice of MFMA work (~1 us) to land.  Fragments
+//     are double-buffered in registers across the barriers, so the MFMA pipe
+//     does not drain at a slice boundary.  Two workgroup barriers per k-slice.
+//   * The loader permutes the rows of the B tile inside LDS so that the four
+//     MFMA tiles of a lane hold four consecutive columns of C: the epilogue
+//     reads and writes C with 16-byte accesses (512 contiguous bytes per
+//     half-wave) without any cross-lane shuffle.
+//   * Workgroups are persistent (one per CU); ids are dealt round-robin to the 8
+//     XCDs (one L2 each): the 32 workgroups of an XCD walk 32 consecutive tiles
+//     of a raster in which tiles sharing operand panels are neighbours.
 #include "kernels.h"
 
 #include <type_traits>
@@ -47,25 +55,17 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int NUM_XCD = 8;
-constexpr int BK = 64;            // k-slice: one 128-byte LDS row of bf16
-constexpr int NPROD = 256;        // producer threads (the last four wavefronts)
-
-// Workgroup tile BM x BN; consumer wavefronts in a WM x WN grid, each TM x TN
-// MFMA tiles of 32 x 32.  WAVES_PER_SIMD bounds the registers of a wavefront.
-template <int BM_, int BN_, int WM_, int WN_>
-struct Cfg {
-    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
-    static constexpr int NCONS = WM * WN;
-    static constexpr int NT = NCONS * 64 + NPROD;
-    static constexpr int WAVES_PER_SIMD = NT / 256;
-    static constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
-    static constexpr int UA = BM * 8 / NPROD, UB = BN * 8 / NPROD;   // 16-byte chunks per producer thread
-    static constexpr int LDS_BYTES = 0x10000 + (BM + BN) * 128;      // stage 1 sits 64 KiB above stage 0
-    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && (BM + BN) * 128 <= 0x10000 && UA >= 2 && UB >= 2,
-                  "tile shape");
-};
+constexpr int BK = 64;                   // k-slice: one 128-byte LDS row of bf16
+constexpr int BM = 256, BN = 256;        // workgroup tile
+constexpr int TM = 4, TN = 4;            // 32 x 32 MFMA tiles per wavefront (2 x 2 wavefronts)
+constexpr int NT = 256;
+constexpr uint32_t STAGE = 0x10000u;     // bytes of one LDS stage: [A tile 32 KiB][B tile 32 KiB]
+constexpr uint32_t B_OFF = BM * 128;
+constexpr int LDS_BYTES = 2 * STAGE;
+constexpr int EPD = 4;                   // epilogue: blocks of C loads in flight + the one being stored
 
 enum Mode : int { MODE_FWD = 0, MODE_APPLY = 1 };
 
@@ -80,7 +80,7 @@ struct Params {
     int tiles_m, tiles_n;
     int64_t tiles_total;
     int group_m;        // raster: groups of group_m row-tiles, row-tile index fastest inside a group
-    int dbg;            // timing experiments: 2 = skip epilogue, 4 = skip MFMA, 8 = no shadow store
+    int dbg;            // timing experiments: 2 = skip epilogue, 8 = no shadow store
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
@@ -90,39 +90,61 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     return __builtin_bit_cast(uint32_t, h);
 }
 
-// LDS byte offset of the 16-byte chunk c (0..7) of tile row r.  Rows are 128
-// bytes, i.e. half of the 64 banks; the chunk slot is c ^ f(r) with
-// f(r) = ((r >> 1) ^ (r >> 3)) & 7, so that 16 consecutive rows at one chunk
-// index (an MFMA operand read) hit 16 distinct bank groups.
-// Two identities keep the per-slice address arithmetic to one XOR:
-//   f(r + 32) = f(r) ^ 4, f(r + 64) = f(r): rows 64 apart differ by a constant;
-//   chunk (2 ks + g) of row r sits at lds_byte(r, g) ^ (32 ks).
-// An LDS stage is [A tile 32 KiB][B tile 32 KiB]; stage 1 is at +64 KiB, so a
-// stage flip is an XOR of the base offset with 0x10000.
-__device__ __forceinline__ uint32_t lds_byte(int r, int c)
+// Chunk-slot swizzle of tile row r: chunk c of the row sits in slot c ^ swz(r).
+// 16 consecutive rows at one chunk index (an MFMA operand read) hit 16 distinct
+// bank groups.  swz(r + 32) = swz(r) ^ 4 and swz(r + 64) = swz(r).
+__device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ (r >> 3)) & 7; }
+// LDS byte offset of chunk c (0..7) of tile row r (128-byte rows).  Chunk
+// (2 ks + g) of row r sits at lds_byte(r, g) ^ (32 ks).
+__device__ __forceinline__ uint32_t lds_byte(int r, int c) { return (uint32_t)(r * 128 + ((c ^ swz(r)) << 4)); }
+
+// A wave-uniform 64-bit value as the compiler can see it (scalar registers).
+__device__ __forceinline__ uint64_t uniform64(uint64_t a)
 {
-    return (uint32_t)(r * 128 + (((c ^ (r >> 1) ^ (r >> 3)) & 7) << 4));
+    // (the builtin returns a signed int: narrow to 32 unsigned bits before widening)
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    return ((uint64_t)hi << 32) | (uint64_t)lo;
 }
 
-template <class C>
-struct Slice {  // registers of one k-slice in flight in a producer thread
-    u32x4 a[C::UA];
-    u32x4 b[C::UB];
-};
-
-template <int MODE, class C>
-__global__ __launch_bounds__(C::NT, C::WAVES_PER_SIMD) void sf_gemm_kernel(Params p)
+// 16 bytes per lane from global memory straight into LDS: lane l's bytes land at
+// LDS address lds_addr + 16 l (lds_addr wave-uniform, in M0); the global address
+// is gbase (uniform) + voff (per lane).  Issued as inline assembly so that the
+// compiler's wait-count insertion does not tie every later LDS read to it; the
+// caller waits (vmcnt) before the barrier that publishes the data.
+__device__ __forceinline__ void load_to_lds_16(uint32_t lds_addr, uint64_t gbase, uint32_t voff)
 {
-    constexpr int BM = C::BM, BN = C::BN, NCONS = C::NCONS, TM = C::TM, TN = C::TN;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase)
+                 : "memory");
+}
+// One accumulator element out of the accumulation registers.  Written as
+// assembly because the compiler otherwise copies whole 16-register tiles (64
+// registers per block of the epilogue) to ordinary registers up front.  The
+// caller guarantees that the MFMA that wrote the element has retired
+// (mfma_results_settle).
+__device__ __forceinline__ float acc_read(float element)
+{
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(element));
+    return v;
+}
+// More wait states than the longest MFMA needs to write back its result.
+__device__ __forceinline__ void mfma_results_settle()
+{
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+}
+__device__ __forceinline__ void wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <int MODE>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void sf_gemm_kernel(Params p)
+{
     extern __shared__ u32x4 smem[];
-    uint16_t* lds = reinterpret_cast<uint16_t*>(smem);
+    const char* const lds_bytes = reinterpret_cast<const char*>(smem);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
 
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
-    // the wavefront index as a scalar: the role branch below is then a uniform
-    // (scalar) branch, never an exec-masked region around the barriers
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool producer = wave >= NCONS;
-    static_assert(C::NT % 256 == 0, "whole wavefronts per SIMD");
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar
+    const int wm0 = (wave >> 1) * (TM * 32), wn0 = (wave & 1) * (TN * 32);
 
     // ---- persistent schedule ------------------------------------------------
     const int64_t x = blockIdx.x % NUM_XCD, wi = blockIdx.x / NUM_XCD, per_xcd = gridDim.x / NUM_XCD;
@@ -143,236 +165,255 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_SIMD) void sf_gemm_kernel(Param
         n0 = (r / gm) * BN;
     };
 
-    // One barrier per k-slice step, executed by both roles (1 + 2 * ceil(S / 2)
-    // barriers each).  At step s the consumers run the MFMAs of slice s out of
-    // LDS stage s & 1 (and the epilogue when the slice ends a tile); the
-    // producers move slice s+1 from register set (s+1) & 1 into LDS stage
-    // (s+1) & 1 and then issue the loads of slice s+3 into the freed set.  The
-    // roles are separate loops so that a wavefront's registers hold either
-    // accumulators or slices, never both.
-    if (producer) {
-        // Every load is unconditional (rows outside the matrix are clamped to the
-        // last row: they only feed accumulators that are never stored; k is
-        // zero-padded), so the number of loads in flight is a compile-time fact
-        // and the wait before staging a slice leaves the next slice's loads
-        // outstanding.  Past the last slice the cursor stays on a valid tile and
-        // the loads are simply never staged.
-        const int ptid = tid - NCONS * 64;
-        const int prow = ptid >> 3, pc = ptid & 7;
-        const uint32_t pitchA = (uint32_t)p.lda * 2u, pitchB = (uint32_t)p.ldb * 2u;
-        Slice<C> sl[2];
-        int64_t iss_q = 0, iss_k = 0, iss_m0 = 0, iss_n0 = 0;
-        const char* baseA = nullptr;   // address of (row 0, current k-slice) of the tile being loaded
-        const char* baseB = nullptr;
-        int lastA = 0, lastB = 0;      // last valid row of the tile
-        auto enter_tile = [&]() {
-            baseA = reinterpret_cast<const char*>(p.A) + iss_m0 * p.lda * 2;
-            baseB = reinterpret_cast<const char*>(p.B) + iss_n0 * p.ldb * 2;
-            lastA = (int)(p.M - iss_m0 < BM ? p.M - iss_m0 : BM) - 1;
-            lastB = (int)(p.N - iss_n0 < BN ? p.N - iss_n0 : BN) - 1;
-        };
-        auto issue = [&](Slice<C>& s) {
+    // Which row of the B tile sits in LDS row r.  MFMA tile tb of a wavefront takes
+    // its 32 columns from LDS rows 32 tb .. 32 tb + 31 of the wavefront's 128; those
+    // rows hold tile rows 4 l + tb (l = 0..31), so that a lane ends up with four
+    // CONSECUTIVE columns of C in its four tiles (one 16-byte access per row in
+    // the epilogue, no cross-lane shuffles).  The loader is free to do this: each
+    // lane of a direct load supplies its own global address.
+    auto b_row_of = [](int r) { return (r & ~127) | ((r & 31) << 2) | ((r >> 5) & 3); };
+
+    // ---- loader ---------------------------------------------------------------
+    // A k-slice of a tile is 32 blocks of 8 rows for each operand; wavefront w
+    // loads blocks 8w..8w+7 of both.  Lane l of block b fills slot l & 7 of row
+    // 8b + (l >> 3), i.e. fetches chunk (l & 7) ^ swz(row).  Rows past the end of
+    // the matrix are clamped to its last row: they only feed accumulators that
+    // are never stored; k is zero-padded.
+    const uint32_t pitchA = (uint32_t)p.lda * 2u, pitchB = (uint32_t)p.ldb * 2u;
+    uint32_t offA[8], offB[8];
+    uint64_t gA = 0, gB = 0;           // address of (row 0, current k-slice) of the tile being loaded
+    int64_t iss_q = 0, iss_k = 0;
+    uint32_t iss_stage = 0;
+    auto enter_tile = [&](int64_t ordinal) {
+        int64_t m0, n0;
+        tile_origin(ordinal, m0, n0);
+        gA = uniform64(reinterpret_cast<uint64_t>(p.A) + (uint64_t)(m0 * p.lda * 2));
+        gB = uniform64(reinterpret_cast<uint64_t>(p.B) + (uint64_t)(n0 * p.ldb * 2));
+        const int lastA = (int)(p.M - m0 < BM ? p.M - m0 : BM) - 1;
+        const int lastB = (int)(p.N - n0 < BN ? p.N - n0 : BN) - 1;
 #pragma unroll
-            for (int i = 0; i < C::UA; ++i) {
-                const int r = prow + 32 * i < lastA ? prow + 32 * i : lastA;
-                s.a[i] = *reinterpret_cast<const u32x4*>(baseA + ((uint32_t)r * pitchA + (uint32_t)pc * 16u));
-            }
-#pragma unroll
-            for (int i = 0; i < C::UB; ++i) {
-                const int r = prow + 32 * i < lastB ? prow + 32 * i : lastB;
-                s.b[i] = *reinterpret_cast<const u32x4*>(baseB + ((uint32_t)r * pitchB + (uint32_t)pc * 16u));
-            }
-            baseA += BK * 2;
-            baseB += BK * 2;
-            ++iss_q;
-            if (++iss_k == nk) {
-                iss_k = 0;
-                if (iss_q < S) tile_origin(iss_q / nk, iss_m0, iss_n0);
-                enter_tile();
-            }
-        };
-        // LDS write offsets: rows prow + 32 i; even / odd i differ by the constant of
-        // the swizzle, the rest is an immediate offset.
-        char* const lds_bytes = reinterpret_cast<char*>(lds);
-        uint32_t wr0 = lds_byte(prow, pc), wr1 = lds_byte(prow + 32, pc) - 32 * 128;
-        auto stash = [&](const Slice<C>& s) {   // into the stage wr0 / wr1 currently point at, then flip them
-#pragma unroll
-            for (int i = 0; i < C::UA; ++i)
-                *reinterpret_cast<u32x4*>(lds_bytes + ((i & 1) ? wr1 : wr0) + i * 32 * 128) = s.a[i];
-#pragma unroll
-            for (int i = 0; i < C::UB; ++i)
-                *reinterpret_cast<u32x4*>(lds_bytes + ((i & 1) ? wr1 : wr0) + i * 32 * 128 + BM * 128) = s.b[i];
-            wr0 ^= 0x10000u;
-            wr1 ^= 0x10000u;
-        };
-        tile_origin(0, iss_m0, iss_n0);
-        enter_tile();
-        issue(sl[0]);
-        issue(sl[1]);
-        stash(sl[0]);                  // slice 0 -> stage 0
-        issue(sl[0]);
-        __syncthreads();
-        for (int64_t s = 0; s < S; s += 2) {
-            stash(sl[1]);              // slice s+1 -> stage 1
-            issue(sl[1]);
-            __syncthreads();
-            stash(sl[0]);              // slice s+2 -> stage 0
-            issue(sl[0]);
-            __syncthreads();
+        for (int i = 0; i < 8; ++i) {
+            const int r = 8 * (8 * wave + i) + (lane >> 3);   // LDS row
+            const uint32_t c16 = (uint32_t)(((lane & 7) ^ swz(r)) << 4);
+            offA[i] = (uint32_t)(r < lastA ? r : lastA) * pitchA + c16;
+            const int rb = b_row_of(r);                        // tile row of B kept in that LDS row
+            offB[i] = (uint32_t)(rb < lastB ? rb : lastB) * pitchB + c16;
         }
-    } else {
-        const int wm0 = (wave / C::WN) * (TM * 32), wn0 = (wave % C::WN) * (TN * 32);
-        floatx16 acc[TM][TN];
+    };
+    // The 16 loads of a slice are issued one at a time (issue_one(0..15)) so that
+    // they can be interleaved with MFMAs: a burst of loads blocks the wavefront in
+    // the memory-issue stage while the MFMA pipe runs dry.
+    auto issue_one = [&](int j) {
+        const uint32_t dst = lds_base + iss_stage + (uint32_t)(8 * wave) * 1024u;
+        if (j < 8)
+            load_to_lds_16(dst + j * 1024u, gA, offA[j & 7]);
+        else
+            load_to_lds_16(dst + B_OFF + (j - 8) * 1024u, gB, offB[j & 7]);
+    };
+    auto issue_done = [&]() {   // advance the load cursor by one slice
+        gA += BK * 2;
+        gB += BK * 2;
+        iss_stage ^= STAGE;
+        ++iss_q;
+        if (++iss_k == nk) {
+            iss_k = 0;
+            if (iss_q < S) {
+                enter_tile(iss_q / nk);
+            } else {   // past the last slice: stay on the last tile (such loads are never read)
+                gA -= (uint64_t)nk * (BK * 2);
+                gB -= (uint64_t)nk * (BK * 2);
+            }
+        }
+    };
+    auto issue = [&]() {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) issue_one(j);
+        issue_done();
+    };
+
+    // ---- MFMA side ------------------------------------------------------------
+    floatx16 acc[TM][TN];   // defined by the first MFMAs of each tile (zero addend)
+
+    // LDS read offsets of this lane: chunk g of rows wm0 + l32 (+32) of the A tile
+    // and wn0 + l32 (+32) of the B tile, in the stage being read.
+    uint32_t ra0 = lds_byte(wm0 + l32, g), ra1 = lds_byte(wm0 + 32 + l32, g) - 32 * 128;
+    uint32_t rb0 = lds_byte(wn0 + l32, g) + B_OFF, rb1 = lds_byte(wn0 + 32 + l32, g) - 32 * 128 + B_OFF;
+    struct Frags {
+        bf16x8 a[TM], b[TN];
+    };
+    auto read_frags = [&](Frags& f, int ks) {   // k-step ks (16 of k) of the stage ra / rb point at
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+            f.a[a] = *reinterpret_cast<const bf16x8*>(lds_bytes + (((a & 1) ? ra1 : ra0) ^ (32u * ks)) + a * 32 * 128);
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+            f.b[b] = *reinterpret_cast<const bf16x8*>(lds_bytes + (((b & 1) ? rb1 : rb0) ^ (32u * ks)) + b * 32 * 128);
+    };
+    auto mfma_step = [&](const Frags& f) {
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
             for (int b = 0; b < TN; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a], f.b[b], acc[a][b], 0, 0, 0);
+    };
+    auto mfma_step_first = [&](const Frags& f) {   // first k-step of a tile: accumulators start from zero
+        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-        int64_t con_k = 0, con_tile = 0, cur_m0 = 0, cur_n0 = 0;
-        tile_origin(0, cur_m0, cur_n0);
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a], f.b[b], zero, 0, 0, 0);
+    };
+    auto flip_stage = [&]() {
+        ra0 ^= STAGE;
+        ra1 ^= STAGE;
+        rb0 ^= STAGE;
+        rb1 ^= STAGE;
+    };
 
-        // LDS read offsets of this lane: chunk g of rows wm0 + l32 (+32) of the A
-        // tile and wn0 + l32 (+32) of the B tile, in the stage being consumed.
-        const char* const lds_bytes = reinterpret_cast<const char*>(lds);
-        uint32_t ra0 = lds_byte(wm0 + l32, g), ra1 = lds_byte(wm0 + 32 + l32, g) - 32 * 128;
-        uint32_t rb0 = lds_byte(wn0 + l32, g) + BM * 128, rb1 = lds_byte(wn0 + 32 + l32, g) - 32 * 128 + BM * 128;
-        auto mfma_slice = [&]() {      // MFMAs of the stage ra / rb point at, then flip them
+    // Epilogue of one tile.  Register i of lane (g, l32) of MFMA tile (ta, tb) is
+    // row 32 ta + 8 (i / 4) + 4 g + i % 4, column 4 l32 + tb of the wavefront's
+    // 128 x 128 block (see b_row_of): for fixed (ta, i) a lane owns 4 consecutive
+    // columns, the 32 lanes of a half-wave 512 contiguous bytes of one row of C,
+    // the other half-wave the row 4 below.  C is addressed through a raw buffer
+    // descriptor based at the wavefront's corner of the tile: the row offset is
+    // scalar, the lane offset one register, so no address registers are live
+    // while loads are in flight.  Rows of C and of its bf16 copy are 16- resp.
+    // 8-byte aligned (checked by the launcher).
+    auto make_rsrc = [&](const void* base) {
+        return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(uniform64(reinterpret_cast<uint64_t>(base))),
+                                                 0, 0xffffffff, 0x00020000);
+    };
+    auto epilogue_tile = [&](int64_t m0, int64_t n0, auto guard_tag) {
+        constexpr bool GUARD = decltype(guard_tag)::value;
+        const auto crs = make_rsrc(p.C + (m0 + wm0) * p.ldc + n0 + wn0);
+        const bool has_shadow = p.shadow && !(p.dbg & 8);
+        const auto srs = make_rsrc(has_shadow ? p.shadow + (m0 + wm0) * p.ld_shadow + n0 + wn0 : p.shadow);
+        const int rows_left = (int)(p.M - (m0 + wm0) < 4 * BM ? p.M - (m0 + wm0) : 4 * BM) - 4 * g;   // for this lane
+        const uint32_t row_c = (uint32_t)p.ldc * 4u, row_s = (uint32_t)p.ld_shadow * 2u;
+        const uint32_t lane_c = (uint32_t)(4 * g) * row_c + (uint32_t)l32 * 16u;
+        const uint32_t lane_s = (uint32_t)(4 * g) * row_s + (uint32_t)l32 * 8u;
+        const bool col_ok = !GUARD || (n0 + wn0 + 4 * l32 < p.N);   // N % 4 == 0: all four columns or none
+        // One block = 16 rows of one ta (8 accesses of 16 bytes per lane).  The loads
+        // of the next EPD - 1 blocks are in flight while a block is combined and
+        // stored.
+        constexpr int NQ = 2 * TM;
+        u32x4 w[EPD][8];
+        mfma_results_settle();
+        auto load_block = [&](int q, u32x4* dst) {
 #pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
-                bf16x8 fa[TM], fb[TN];
-#pragma unroll
-                for (int a = 0; a < TM; ++a)
-                    fa[a] = *reinterpret_cast<const bf16x8*>(lds_bytes + (((a & 1) ? ra1 : ra0) ^ (32u * ks)) +
-                                                             a * 32 * 128);
-#pragma unroll
-                for (int b = 0; b < TN; ++b)
-                    fb[b] = *reinterpret_cast<const bf16x8*>(lds_bytes + (((b & 1) ? rb1 : rb0) ^ (32u * ks)) +
-                                                             b * 32 * 128);
-#pragma unroll
-                for (int a = 0; a < TM; ++a)
-#pragma unroll
-                    for (int b = 0; b < TN; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+            for (int e = 0; e < 8; ++e) {
+                const int i = (q & 1) * 8 + e, dr = (q >> 1) * 32 + 8 * (i / 4) + (i % 4);
+                dst[e] = u32x4{0u, 0u, 0u, 0u};
+                if (col_ok && (!GUARD || dr < rows_left))
+                    dst[e] = __builtin_amdgcn_raw_buffer_load_b128(crs, lane_c, (uint32_t)dr * row_c, 0);
             }
         };
-        auto flip_stage = [&]() {
-            ra0 ^= 0x10000u;
-            ra1 ^= 0x10000u;
-            rb0 ^= 0x10000u;
-            rb1 ^= 0x10000u;
-        };
-
-        // Epilogue of one tile.  Register i of lane (g, l32) of a 32x32 MFMA tile
-        // is row 8*(i/4) + 4*g + i%4, column l32.  Two column-adjacent tiles are
-        // first combined with v_permlane32_swap (upper half of one register <->
-        // lower half of the other): afterwards one register holds ONE row across
-        // 64 consecutive columns (lane = column), the other the row 4 below.  Every
-        // access of C is then 256 contiguous bytes (128 for the bf16 copy) at a
-        // uniform row address plus a per-lane column offset.
-        static_assert(TN % 2 == 0, "tiles are paired along n");
-        // C is addressed through a raw buffer descriptor based at this wave's corner
-        // of the tile: row offsets are scalar, the column offset is one register per
-        // lane, so no per-row address registers are live while loads are in flight.
-        auto make_rsrc = [&](const void* base) {
-            const uint64_t a = reinterpret_cast<uint64_t>(base);
-            // (the builtin returns a signed int: narrow to 32 unsigned bits before widening)
-            const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
-            const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
-            const uint64_t u = ((uint64_t)hi << 32) | (uint64_t)lo;
-            return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(u), 0, 0xffffffff, 0x00020000);
-        };
-        auto epilogue_tile = [&](int64_t m0, int64_t n0, auto guard_tag) {
-            constexpr bool GUARD = decltype(guard_tag)::value;
-            const auto crs = make_rsrc(p.C + (m0 + wm0) * p.ldc + n0 + wn0);
-            const bool has_shadow = p.shadow && !(p.dbg & 8);
-            const auto srs = make_rsrc(has_shadow ? p.shadow + (m0 + wm0) * p.ld_shadow + n0 + wn0 : p.shadow);
-            const int64_t rows_left = p.M - (m0 + wm0);
-            const uint32_t row_c = (uint32_t)p.ldc * 4u, row_s = (uint32_t)p.ld_shadow * 2u;
-            // One block = 32 rows x 64 columns (two column-adjacent MFMA tiles).  The loads of
-            // block q+1 are in flight while block q is combined and stored.
-            constexpr int NQ = TM * (TN / 2);
-            float w[2][32];
-            auto load_block = [&](int q, float* dst) {
-                const int ta = q / (TN / 2), tp = q % (TN / 2);
-                const bool col_ok = !GUARD || (n0 + wn0 + tp * 64 + lane < p.N);
-                const uint32_t coff = (uint32_t)(tp * 64 + lane);
+        if (MODE == MODE_APPLY) {
 #pragma unroll
-                for (int e = 0; e < 32; ++e) {
-                    const int i = e / 2, dr = ta * 32 + 8 * (i / 4) + (i % 4) + 4 * (e & 1);
-                    dst[e] = 0.f;
-                    if (col_ok && (!GUARD || dr < rows_left))
-                        dst[e] = __uint_as_float(
-                            __builtin_amdgcn_raw_buffer_load_b32(crs, coff * 4u, (uint32_t)dr * row_c, 0));
-                }
-            };
-            if (MODE == MODE_APPLY) load_block(0, w[0]);
+            for (int q = 0; q < EPD - 1 && q < NQ; ++q) load_block(q, w[q % EPD]);
+        }
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) {
-                const int ta = q / (TN / 2), tp = q % (TN / 2);
-                if (MODE == MODE_APPLY && q + 1 < NQ) load_block(q + 1, w[(q + 1) & 1]);
-                const bool col_ok = !GUARD || (n0 + wn0 + tp * 64 + lane < p.N);
-                const uint32_t coff = (uint32_t)(tp * 64 + lane);
+        for (int q = 0; q < NQ; ++q) {
+            const int ta = q >> 1;
+            if (MODE == MODE_APPLY && q + EPD - 1 < NQ) load_block(q + EPD - 1, w[(q + EPD - 1) % EPD]);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    // (element first into a scalar: bit-casting a vector element directly is
-                    // miscompiled by this toolchain)
-                    const float lo = acc[ta][2 * tp][i], hi = acc[ta][2 * tp + 1][i];
-                    const auto sw =
-                        __builtin_amdgcn_permlane32_swap(__float_as_uint(lo), __float_as_uint(hi), false, false);
-                    const uint32_t s0 = sw[0], s1 = sw[1];
-#pragma unroll
-                    for (int half = 0; half < 2; ++half) {
-                        const float val = __uint_as_float(half ? s1 : s0);
-                        const int dr = ta * 32 + 8 * (i / 4) + (i % 4) + 4 * half;
-                        if (col_ok && (!GUARD || dr < rows_left)) {
-                            if (MODE == MODE_FWD) {
-                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), crs, coff * 4u,
-                                                                      (uint32_t)dr * row_c, 0);
-                            } else {
-                                const float nw = w[q & 1][2 * i + half] - p.eta * val;
-                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(nw), crs, coff * 4u,
-                                                                      (uint32_t)dr * row_c, 0);
-                                if (has_shadow)
-                                    __builtin_amdgcn_raw_buffer_store_b16((uint16_t)(pack_bf16(nw, 0.f) & 0xffffu),
-                                                                          srs, coff * 2u, (uint32_t)dr * row_s, 0);
-                            }
+            for (int e = 0; e < 8; ++e) {
+                const int i = (q & 1) * 8 + e, dr = ta * 32 + 8 * (i / 4) + (i % 4);
+                const float v0 = acc_read(acc[ta][0][i]), v1 = acc_read(acc[ta][1][i]);
+                const float v2 = acc_read(acc[ta][2][i]), v3 = acc_read(acc[ta][3][i]);
+                if (col_ok && (!GUARD || dr < rows_left)) {
+                    if (MODE == MODE_FWD) {
+                        const u32x4 out = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2),
+                                           __float_as_uint(v3)};
+                        __builtin_amdgcn_raw_buffer_store_b128(out, crs, lane_c, (uint32_t)dr * row_c, 0);
+                    } else {
+                        const uint32_t o0 = w[q % EPD][e][0], o1 = w[q % EPD][e][1], o2 = w[q % EPD][e][2],
+                                       o3 = w[q % EPD][e][3];
+                        const float n0f = __uint_as_float(o0) - p.eta * v0, n1f = __uint_as_float(o1) - p.eta * v1;
+                        const float n2f = __uint_as_float(o2) - p.eta * v2, n3f = __uint_as_float(o3) - p.eta * v3;
+                        const u32x4 out = {__float_as_uint(n0f), __float_as_uint(n1f), __float_as_uint(n2f),
+                                           __float_as_uint(n3f)};
+                        __builtin_amdgcn_raw_buffer_store_b128(out, crs, lane_c, (uint32_t)dr * row_c, 0);
+                        if (has_shadow) {
+                            const u32x2 sh = {pack_bf16(n0f, n1f), pack_bf16(n2f, n3f)};
+                            __builtin_amdgcn_raw_buffer_store_b64(sh, srs, lane_s, (uint32_t)dr * row_s, 0);
                         }
                     }
                 }
             }
-        };
-        auto epilogue = [&](int64_t m0, int64_t n0) {
+        }
+    };
+
+    // ---- pipeline ---------------------------------------------------------------
+    // Slice s lives in stage s & 1.  In the last k-step of slice s, after every
+    // wavefront has read that step's fragments (so stage s & 1 is free) and the
+    // loads of slice s+1 have landed, the loads of slice s+2 are issued and the
+    // first fragments of slice s+1 are read; the MFMAs of the last k-step cover
+    // both latencies.
+    Frags f0, f1;
+    enter_tile(0);
+    issue();
+    wait_all_vmem();
+    __syncthreads();
+    issue();
+    read_frags(f0, 0);
+    // One k-slice (slice s, living in stage s & 1; f0 holds its first fragments).
+    // The 16 direct loads of slice s+2 are spread over the last two k-steps, one
+    // load per two MFMAs: a burst of loads blocks the wavefront in the
+    // memory-issue stage while the MFMA pipe runs dry.  They are unconditional
+    // (past the last slice they re-fetch the last tile into a stage nobody reads).
+    // Two barriers: A, after every wavefront has read the last fragments of
+    // slice s (stage s & 1 may be overwritten); B, after the loads of slice s+1
+    // have landed (they were issued one slice earlier; the 8 loads issued since
+    // A may still be in flight: vmcnt counts in order).
+    auto mfma_one = [&](const Frags& f, int j) {
+        acc[j / TN][j % TN] =
+            __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[j / TN], f.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
+    };
+    auto slice_body = [&](auto first_tag) {
+        read_frags(f1, 1);
+        if constexpr (decltype(first_tag)::value)
+            mfma_step_first(f0);
+        else
+            mfma_step(f0);
+        read_frags(f0, 2);
+        mfma_step(f1);
+        read_frags(f1, 3);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) mfma_one(f0, j);
+        __syncthreads();                                   // A
+#pragma unroll
+        for (int j = 8; j < 16; ++j) {
+            mfma_one(f0, j);
+            issue_one(j - 8);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        __syncthreads();                                   // B
+        flip_stage();
+        read_frags(f0, 0);   // (after the last slice: a stage nobody uses)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            mfma_one(f1, j);
+            if (j & 1) issue_one(8 + j / 2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        issue_done();
+    };
+    for (int64_t t = 0; t < n_my; ++t) {
+        int64_t m0, n0;
+        tile_origin(t, m0, n0);
+        slice_body(std::true_type{});
+        for (int64_t k = 1; k < nk; ++k) slice_body(std::false_type{});
+        if (!(p.dbg & 2)) {
             if ((m0 + BM <= p.M) && (n0 + BN <= p.N))
                 epilogue_tile(m0, n0, std::false_type{});
             else
                 epilogue_tile(m0, n0, std::true_type{});
-        };
-
-        auto consume = [&](int64_t s) {
-            if (!(p.dbg & 4)) mfma_slice();
-            flip_stage();
-            if (++con_k == nk) {
-                con_k = 0;
-                if (!(p.dbg & 2)) epilogue(cur_m0, cur_n0);
-                ++con_tile;
-                if (con_tile < n_my) tile_origin(con_tile, cur_m0, cur_n0);
-#pragma unroll
-                for (int a = 0; a < TM; ++a)
-#pragma unroll
-                    for (int b = 0; b < TN; ++b)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-            }
-        };
-        __syncthreads();
-        for (int64_t s = 0; s < S; s += 2) {
-            consume(s);
-            __syncthreads();
-            if (s + 1 < S) consume(s + 1);
-            __syncthreads();
         }
     }
+    wait_all_vmem();   // no direct load may be in flight when the workgroup's LDS is released
 }
 
 // src[rows_src][cols] (bf16, row-major) -> dst[cols][pitch]; source rows
@@ -421,31 +462,35 @@ __global__ __launch_bounds__(256) void pad_rows_bf16_kernel(const SrcT* __restri
     }
 }
 
-int g_forward_dbg = 0;   // timing experiments only: 2 = no epilogue, 4 = no MFMA
+int g_forward_dbg = 0;   // timing experiments only: 2 = no epilogue, 8 = no shadow store
 int g_apply_dbg = 0;
 
-template <int MODE, class C>
+template <int MODE>
 hipError_t launch(Params p, hipStream_t stream)
 {
-    constexpr int BM = C::BM, BN = C::BN;
     p.tiles_m = (int)((p.M + BM - 1) / BM);
     p.tiles_n = (int)((p.N + BN - 1) / BN);
     p.tiles_total = (int64_t)p.tiles_m * p.tiles_n;
     if (p.group_m <= 0 || p.group_m > p.tiles_m) p.group_m = p.tiles_m;
-    // 32-bit in-tile byte offsets in the loaders
+    // 32-bit in-tile byte offsets in the loaders and in the epilogue
     if (p.lda * 2 * BM >= (1LL << 31) || p.ldb * 2 * BN >= (1LL << 31) || p.ldc * 4 * BM >= (1LL << 31))
         return hipErrorInvalidValue;
-    if (p.K % BK != 0 || p.lda % BK != 0 || p.ldb % BK != 0) return hipErrorInvalidValue;
+    // 16-byte accesses of C, 8-byte accesses of its bf16 copy
+    if (reinterpret_cast<uintptr_t>(p.C) % 16 != 0 || p.ldc % 4 != 0 || p.N % 4 != 0) return hipErrorInvalidValue;
+    if (p.shadow && (reinterpret_cast<uintptr_t>(p.shadow) % 8 != 0 || p.ld_shadow % 4 != 0))
+        return hipErrorInvalidValue;
+    if (p.K <= 0 || p.K % BK != 0 || p.lda % BK != 0 || p.ldb % BK != 0 || p.lda < p.K || p.ldb < p.K)
+        return hipErrorInvalidValue;
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sf_gemm_kernel<MODE, C>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sf_gemm_kernel<MODE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     int64_t grid = 256;                      // one persistent workgroup per CU
     if (p.tiles_total < grid) grid = (p.tiles_total + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
-    hipLaunchKernelGGL((sf_gemm_kernel<MODE, C>), dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, stream, p);
+    hipLaunchKernelGGL((sf_gemm_kernel<MODE>), dim3((unsigned)grid), dim3(NT), LDS_BYTES, stream, p);
     return hipGetLastError();
 }
 
@@ -491,7 +536,7 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
     p.K = pitch;
     p.group_m = 0;               // all batch tiles of one class tile are neighbours (they share the W tile)
     p.dbg = g_forward_dbg;
-    return launch<MODE_FWD, Cfg<256, 128, 2, 2>>(p, stream);
+    return launch<MODE_FWD>(p, stream);
 }
 
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D) { return (J + D) * bf16_pitch(N) * 2; }
@@ -518,7 +563,7 @@ hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, const uint16_t* U, co
     p.eta = eta;
     p.group_m = 8;               // 8 row-tiles x 4 column tiles under one L2 at a time
     p.dbg = g_apply_dbg;
-    return launch<MODE_APPLY, Cfg<128, 256, 2, 2>>(p, stream);
+    return launch<MODE_APPLY>(p, stream);
 }
 
 }  // namespace sfb
