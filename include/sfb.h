@@ -176,8 +176,10 @@ typedef struct {
 int sfb_profile_enable(sfb_ctx* ctx, int on);
 int sfb_profile_collect(sfb_ctx* ctx, sfb_kernel_time* out, int max_entries, int* count);
 
-/* Benchmark knob: picks a tile variant of the bf16 forward / apply kernels
- * (process-wide; -1 = the default).  Every variant computes the same sums. */
+/* Timing-experiment knob of the bf16 forward / apply kernel (process-wide;
+ * -1 or 0 = normal operation).  value / 100 is a bit set: 2 = skip the
+ * epilogue (nothing is written), 8 = do not refresh the bf16 working copy.
+ * Results are only valid at 0. */
 void sfb_tune_bf16_variant(int forward_variant, int apply_variant);
 
 #ifdef __cplusplus

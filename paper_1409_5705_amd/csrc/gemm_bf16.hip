@@ -65,6 +65,10 @@ constexpr int NT = 256;
 constexpr uint32_t STAGE = 0x10000u;     // bytes of one LDS stage: [A tile 32 KiB][B tile 32 KiB]
 constexpr uint32_t B_OFF = BM * 128;
 constexpr int LDS_BYTES = 2 * STAGE;
+// Cache policy of the accesses of C and of its bf16 copy: non-temporal (each
+// line is touched once per launch; left at the default policy they sweep the
+// operand panels, which ARE reused, out of the 4 MiB L2 of the XCD).
+constexpr int C_POLICY = 2;
 constexpr int EPD = 4;                   // epilogue: blocks of C loads in flight + the one being stored
 
 enum Mode : int { MODE_FWD = 0, MODE_APPLY = 1 };
@@ -306,7 +310,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                 const int i = (q & 1) * 8 + e, dr = (q >> 1) * 32 + 8 * (i / 4) + (i % 4);
                 dst[e] = u32x4{0u, 0u, 0u, 0u};
                 if (col_ok && (!GUARD || dr < rows_left))
-                    dst[e] = __builtin_amdgcn_raw_buffer_load_b128(crs, lane_c, (uint32_t)dr * row_c, 0);
+                    dst[e] = __builtin_amdgcn_raw_buffer_load_b128(crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
             }
         };
         if (MODE == MODE_APPLY) {
@@ -326,7 +330,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                     if (MODE == MODE_FWD) {
                         const u32x4 out = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2),
                                            __float_as_uint(v3)};
-                        __builtin_amdgcn_raw_buffer_store_b128(out, crs, lane_c, (uint32_t)dr * row_c, 0);
+                        __builtin_amdgcn_raw_buffer_store_b128(out, crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
                     } else {
                         const uint32_t o0 = w[q % EPD][e][0], o1 = w[q % EPD][e][1], o2 = w[q % EPD][e][2],
                                        o3 = w[q % EPD][e][3];
@@ -334,10 +338,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                         const float n2f = __uint_as_float(o2) - p.eta * v2, n3f = __uint_as_float(o3) - p.eta * v3;
                         const u32x4 out = {__float_as_uint(n0f), __float_as_uint(n1f), __float_as_uint(n2f),
                                            __float_as_uint(n3f)};
-                        __builtin_amdgcn_raw_buffer_store_b128(out, crs, lane_c, (uint32_t)dr * row_c, 0);
+                        __builtin_amdgcn_raw_buffer_store_b128(out, crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
                         if (has_shadow) {
                             const u32x2 sh = {pack_bf16(n0f, n1f), pack_bf16(n2f, n3f)};
-                            __builtin_amdgcn_raw_buffer_store_b64(sh, srs, lane_s, (uint32_t)dr * row_s, 0);
+                            __builtin_amdgcn_raw_buffer_store_b64(sh, srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
                         }
                     }
                 }
@@ -561,7 +565,7 @@ hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, const uint16_t* U, co
     p.shadow = W_shadow; p.ld_shadow = bf16_pitch(D);
     p.K = Np;
     p.eta = eta;
-    p.group_m = 8;               // 8 row-tiles x 4 column tiles under one L2 at a time
+    p.group_m = 8;               // 8 row-tiles x 4 column tiles under one L2 at a time (measured best of 1..32)
     p.dbg = g_apply_dbg;
     return launch<MODE_APPLY>(p, stream);
 }
