@@ -421,22 +421,34 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
 }
 
 // src[rows_src][cols] (bf16, row-major) -> dst[cols][pitch]; source rows
-// rows_src..pitch-1 are taken as zero.  64x64 tiles through LDS, 256 threads.
+// rows_src..pitch-1 are taken as zero.  cols % 8 == 0, pitch % 64 == 0.
+// 64x64 tiles through LDS, 256 threads, 16-byte global accesses on both sides
+// (8 lanes cover one 128-byte row segment).
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ src,
                                                              uint16_t* __restrict__ dst, int64_t rows_src,
                                                              int64_t cols, int64_t pitch)
 {
-    __shared__ uint16_t tile[64][64 + 2];
+    constexpr int LP = 72;   // LDS row pitch in elements: 144 bytes, rows stay 16-byte aligned
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * LP];
     const int64_t c0 = (int64_t)blockIdx.x * 64, k0 = (int64_t)blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int r = ty; r < 64; r += 4) {
-        const int64_t k = k0 + r, c = c0 + tx;
-        tile[r][tx] = (k < rows_src && c < cols) ? src[k * cols + c] : (uint16_t)0;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int id = threadIdx.x + 256 * it, r = id >> 3, cc = (id & 7) * 8;
+        const int64_t k = k0 + r, c = c0 + cc;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (k < rows_src && c < cols) v = *reinterpret_cast<const u32x4*>(src + k * cols + c);
+        *reinterpret_cast<u32x4*>(&tile[r * LP + cc]) = v;
     }
     __syncthreads();
-    for (int r = ty; r < 64; r += 4) {
-        const int64_t c = c0 + r, k = k0 + tx;
-        if (c < cols && k < pitch) dst[c * pitch + k] = tile[tx][r];
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int id = threadIdx.x + 256 * it, cr = id >> 3, kc = (id & 7) * 8;
+        const int64_t c = c0 + cr;
+        uint32_t o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            o[i] = (uint32_t)tile[(kc + 2 * i) * LP + cr] | ((uint32_t)tile[(kc + 2 * i + 1) * LP + cr] << 16);
+        if (c < cols) *reinterpret_cast<u32x4*>(dst + c * pitch + k0 + kc) = u32x4{o[0], o[1], o[2], o[3]};
     }
 }
 
