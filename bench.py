@@ -32,6 +32,20 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def profile_traffic_bytes():
+    """Scaled FETCH_SIZE + WRITE_SIZE per launch, by kernel, from the committed rocprofv3 summary."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "mlr_large_bf16_rocprofv3.md")
+    out = {}
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes "):      # "traffic_bytes <kernel> <bytes>"
+                _, name, val = line.split()
+                out[name] = float(val)
+    except OSError:
+        pass
+    return out
+
+
 def cpu_baseline_mlr(cfg, X, y, seed):
     """The oracle, as it stands, on a bounded sample of the workload: the first Js classes
     (softmax over those), all B samples, full D: SF compute + apply.  Scaled to the metric's
@@ -144,13 +158,15 @@ def main():
         kt["mlr_forward_bf16"] += kt["shadow_convert"]
     fwd_ms = kt.get("mlr_forward_bf16", float("nan"))
     app_ms = kt.get("apply_bf16", float("nan"))
+    tr_ms = kt.get("apply_bf16_transpose", float("nan"))
     smx_ms = kt.get("mlr_softmax", float("nan"))
     gemm_flops = 2.0 * B * J * D                             # per GEMM stage
     # algorithmic HBM bytes per launch (the bf16 working copy of W counts: read by forward, written by apply)
     wb = 2 if not args.no_shadow else 4
     fwd_bytes = J * D * wb + B * D * 2 + B * J * 4           # W (copy) read once, X, logits written
     app_bytes = 2 * J * D * 4 + (J * D * 2 if not args.no_shadow else 0) + B * J * 2 + B * D * 2
-    # ^ W read + written once, bf16 copy written, U, V
+    # ^ W read + written once, bf16 copy written, U^T, V^T read
+    tr_bytes = 2 * (B * J * 2 + B * D * 2)                   # U, V read; U^T, V^T written
     smx_bytes = B * J * 4 + B * J * 2                        # logits read once, U written
     stages = {
         "forward_gemm": {"ms": fwd_ms, "tflops": gemm_flops / fwd_ms / 1e9,
@@ -158,19 +174,27 @@ def main():
                          "hbm_gbs": fwd_bytes / fwd_ms / 1e6, "hbm_frac": fwd_bytes / fwd_ms / 1e6 / PEAK_HBM_GBS},
         "softmax": {"ms": smx_ms, "hbm_gbs": smx_bytes / smx_ms / 1e6,
                     "hbm_frac": smx_bytes / smx_ms / 1e6 / PEAK_HBM_GBS},
+        "apply_transposes": {"ms": tr_ms, "hbm_gbs": tr_bytes / tr_ms / 1e6,
+                             "hbm_frac": tr_bytes / tr_ms / 1e6 / PEAK_HBM_GBS},
         "apply_gemm": {"ms": app_ms, "tflops": gemm_flops / app_ms / 1e9,
                        "mfma_frac": gemm_flops / app_ms / 1e9 / PEAK_BF16_TFLOPS,
                        "hbm_gbs": app_bytes / app_ms / 1e6, "hbm_frac": app_bytes / app_ms / 1e6 / PEAK_HBM_GBS},
     }
     # Roofline of the dominant kernel.  At this shape the forward contraction is
-    # MFMA-bound (512 flop/B) and the apply is HBM-bound (250 flop/B < ridge 312).
+    # MFMA-bound (845 flop/B) and the apply is HBM-bound (200 flop/B < ridge 312).
+    # `traffic`: HBM-side bytes per launch of that kernel from the rocprofv3 --pmc
+    # passes (FETCH_SIZE, WRITE_SIZE, scaled by the copy-kernel calibration) that
+    # the committed summary under profiles/ records; null if it has no such line.
+    traffic = profile_traffic_bytes()
     if fwd_ms >= app_ms:
-        roof = {"kernel": "mlr_forward_bf16", "bound": "mfma", "achieved": stages["forward_gemm"]["tflops"],
+        roof = {"kernel": "sf_gemm_kernel<0> (forward)", "bound": "mfma", "achieved": stages["forward_gemm"]["tflops"],
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": stages["forward_gemm"]["mfma_frac"],
-                "traffic": None}
+                "traffic": traffic.get("sf_gemm_kernel<0>")}
     else:
-        roof = {"kernel": "apply_bf16", "bound": "hbm", "achieved": stages["apply_gemm"]["hbm_gbs"],
-                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": stages["apply_gemm"]["hbm_frac"], "traffic": None}
+        roof = {"kernel": "sf_gemm_kernel<1> (apply)", "bound": "hbm", "achieved": stages["apply_gemm"]["hbm_gbs"],
+                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": stages["apply_gemm"]["hbm_frac"],
+                "traffic": traffic.get("sf_gemm_kernel<1>")}
+    roof["traffic_unit"] = "bytes per launch (rocprofv3 --pmc, separate run; see profiles/)"
 
     out = {
         "metric": "rank-1 SF updates applied/sec (SF compute + reconstruct/apply), MLR J=325k D=10k",

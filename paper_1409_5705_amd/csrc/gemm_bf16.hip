@@ -557,8 +557,8 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
 
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D) { return (J + D) * bf16_pitch(N) * 2; }
 
-hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, const uint16_t* U, const uint16_t* V, int64_t N, int64_t J,
-                             int64_t D, float eta, void* workspace, hipStream_t stream)
+hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, int64_t N, int64_t J, int64_t D,
+                                       void* workspace, hipStream_t stream)
 {
     if (N <= 0 || J <= 0 || D <= 0) return hipSuccess;
     const int64_t Np = bf16_pitch(N);
@@ -568,8 +568,16 @@ hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, const uint16_t* U, co
                        stream, U, Ut, N, J, Np);
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((D + 63) / 64), (unsigned)(Np / 64)), dim3(256), 0,
                        stream, V, Vt, N, D, Np);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, int64_t N, int64_t J, int64_t D, float eta,
+                             const void* workspace, hipStream_t stream)
+{
+    if (N <= 0 || J <= 0 || D <= 0) return hipSuccess;
+    const int64_t Np = bf16_pitch(N);
+    const uint16_t* Ut = static_cast<const uint16_t*>(workspace);
+    const uint16_t* Vt = Ut + J * Np;
     Params p = {};
     p.A = Ut; p.lda = Np; p.M = J;
     p.B = Vt; p.ldb = Np; p.N = D;

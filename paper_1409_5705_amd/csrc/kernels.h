@@ -49,11 +49,14 @@ hipError_t launch_shadow_from_w(const float* W, uint16_t* shadow, int64_t J, int
 hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, float* Z, uint16_t* X_aligned,
                                    int64_t B, int64_t J, int64_t D, hipStream_t stream);
 // W[j][d] -= eta * sum_i U[i][j] * V[i][d];  U bf16 [N][J], V bf16 [N][D], W fp32 [J][D].
-// `workspace` (apply_bf16_workspace_bytes, 256-byte aligned) receives U^T and V^T.
+// Two steps: launch_apply_bf16_transpose writes U^T and V^T into `workspace`
+// (apply_bf16_workspace_bytes, 256-byte aligned), launch_apply_bf16 consumes them.
 // W_shadow (nullable): bf16 copy of W, refreshed with the new values.
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D);
-hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, const uint16_t* U, const uint16_t* V, int64_t N,
-                             int64_t J, int64_t D, float eta, void* workspace, hipStream_t stream);
+hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, int64_t N, int64_t J, int64_t D,
+                                       void* workspace, hipStream_t stream);
+hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, int64_t N, int64_t J, int64_t D, float eta,
+                             const void* workspace, hipStream_t stream);
 // Timing experiments (benchmark sweeps): variant / 100 = debug bits; -1 = normal.
 void set_bf16_variant(int forward_variant, int apply_variant);
 

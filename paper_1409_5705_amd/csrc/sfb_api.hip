@@ -13,6 +13,7 @@
 enum KernelId : int {
     KID_FORWARD_BF16 = 0,
     KID_APPLY_BF16,
+    KID_APPLY_TRANSPOSE,
     KID_SOFTMAX,
     KID_GEMM_F32_STORE,
     KID_GEMM_F32_RMW,
@@ -28,7 +29,7 @@ enum KernelId : int {
     KID_COUNT
 };
 static const char* const kKernelNames[KID_COUNT] = {
-    "mlr_forward_bf16", "apply_bf16", "mlr_softmax", "gemm_f32_store", "gemm_f32_rmw(apply)", "gemm_f32_resid",
+    "mlr_forward_bf16", "apply_bf16", "apply_bf16_transpose", "mlr_softmax", "gemm_f32_store", "gemm_f32_rmw(apply)", "gemm_f32_resid",
     "gemm_f32_shrink", "diff", "dml_scale", "fill", "prox_rows", "power_iteration", "copy", "shadow_convert"};
 
 struct ProfSpan {
@@ -419,9 +420,10 @@ int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const
         uint16_t* Wb = (ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D)
                            ? ctx->shadow_buf
                            : nullptr;
-        SFB_RUN(KID_APPLY_BF16,
-                sfb::launch_apply_bf16(W, Wb, static_cast<const uint16_t*>(U), static_cast<const uint16_t*>(V), N, J, D,
-                                       eta, ctx->ws, ctx->stream));
+        SFB_RUN(KID_APPLY_TRANSPOSE,
+                sfb::launch_apply_bf16_transpose(static_cast<const uint16_t*>(U), static_cast<const uint16_t*>(V), N, J, D,
+                                                 ctx->ws, ctx->stream));
+        SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, Wb, N, J, D, eta, ctx->ws, ctx->stream));
     }
     return SFB_OK;
 }
