@@ -94,6 +94,26 @@ def lib():
         L.sfb_profile_collect.restype = ctypes.c_int
         L.sfb_tune_bf16_variant.argtypes = [ctypes.c_int, ctypes.c_int]
         L.sfb_tune_bf16_variant.restype = None
+        L.sfb_ssp_create.argtypes = [ctypes.POINTER(vp), i32, i32]
+        L.sfb_ssp_create.restype = ctypes.c_int
+        L.sfb_ssp_destroy.argtypes = [vp]
+        L.sfb_ssp_destroy.restype = ctypes.c_int
+        L.sfb_ssp_can_compute.argtypes = [vp, i32]
+        L.sfb_ssp_can_compute.restype = ctypes.c_int
+        L.sfb_ssp_computed.argtypes = [vp, i32]
+        L.sfb_ssp_computed.restype = i64
+        L.sfb_ssp_delivered.argtypes = [vp, i32, i32]
+        L.sfb_ssp_delivered.restype = i64
+        L.sfb_ssp_pop_apply.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i64)]
+        L.sfb_ssp_pop_apply.restype = ctypes.c_int
+        L.sfb_ssp_clock.argtypes = [vp, i32]
+        L.sfb_ssp_clock.restype = i64
+        L.sfb_ssp_tau.argtypes = [vp, i32, i32]
+        L.sfb_ssp_tau.restype = i64
+        L.sfb_ssp_arrived.argtypes = [vp, i32, i32]
+        L.sfb_ssp_arrived.restype = i64
+        L.sfb_ssp_max_staleness_seen.argtypes = [vp]
+        L.sfb_ssp_max_staleness_seen.restype = i64
         _lib = L
     return _lib
 
@@ -267,3 +287,56 @@ class Context:
     def sfb_prox_rows(self, W, mode=SFB_PROX_PROJECT):
         J, D = W.shape
         self._check(lib().sfb_prox_rows(self._h, _ptr(W, "W", dtype=torch.float32), J, D, mode), "sfb_prox_rows")
+
+
+class SspClock:
+    """One sfb_ssp object (include/sfb_ssp.h): counters of BSP / SSP / ASP application of SF sets."""
+
+    def __init__(self, P: int, s: int):
+        self._h = ctypes.c_void_p()
+        rc = lib().sfb_ssp_create(ctypes.byref(self._h), int(P), int(s))
+        if rc != SFB_OK:
+            raise SfbError(rc, "sfb_ssp_create")
+
+    def close(self):
+        if self._h:
+            lib().sfb_ssp_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _chk(self, v, what):
+        if v < 0:
+            raise SfbError(int(v), what)
+        return int(v)
+
+    def sfb_ssp_can_compute(self, p: int) -> bool:
+        return bool(self._chk(lib().sfb_ssp_can_compute(self._h, int(p)), "sfb_ssp_can_compute"))
+
+    def sfb_ssp_computed(self, p: int) -> int:
+        return self._chk(lib().sfb_ssp_computed(self._h, int(p)), "sfb_ssp_computed")
+
+    def sfb_ssp_delivered(self, p: int, q: int) -> int:
+        return self._chk(lib().sfb_ssp_delivered(self._h, int(p), int(q)), "sfb_ssp_delivered")
+
+    def sfb_ssp_pop_apply(self, p: int):
+        """(q, t) of the next SF set worker p has to apply now, or None."""
+        q, t = ctypes.c_int32(), ctypes.c_int64()
+        rc = self._chk(lib().sfb_ssp_pop_apply(self._h, int(p), ctypes.byref(q), ctypes.byref(t)), "sfb_ssp_pop_apply")
+        return (q.value, t.value) if rc else None
+
+    def sfb_ssp_clock(self, p: int) -> int:
+        return self._chk(lib().sfb_ssp_clock(self._h, int(p)), "sfb_ssp_clock")
+
+    def sfb_ssp_tau(self, p: int, q: int) -> int:
+        return self._chk(lib().sfb_ssp_tau(self._h, int(p), int(q)), "sfb_ssp_tau")
+
+    def sfb_ssp_arrived(self, p: int, q: int) -> int:
+        return self._chk(lib().sfb_ssp_arrived(self._h, int(p), int(q)), "sfb_ssp_arrived")
+
+    def sfb_ssp_max_staleness_seen(self) -> int:
+        return self._chk(lib().sfb_ssp_max_staleness_seen(self._h), "sfb_ssp_max_staleness_seen")

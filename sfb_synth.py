@@ -112,3 +112,23 @@ def sc_dictionary(J, D, seed):
 def sc_batch(D, B, seed, step=0):
     g = _rng(seed, 6000, step)
     return g.standard_normal((B, D), dtype=np.float32)
+
+
+def ssp_attempts(P, n, seed):
+    """n seeded scheduling attempts for a simulation of P workers exchanging SF sets.
+
+    Each attempt is ("compute", p) - worker p tries to compute its next SF set - or
+    ("deliver", p, q) - the transport tries to hand worker p the next set of worker q.
+    The draws know nothing of the consistency rules: whether an attempt takes effect is
+    for the simulator (the library's counters on one side, the oracle on the other).
+    """
+    g = _rng(seed, 7000)
+    out = []
+    for _ in range(n):
+        if P == 1 or g.random() < 0.4:
+            out.append(("compute", int(g.integers(P))))
+        else:
+            p = int(g.integers(P))
+            q = int(g.integers(P - 1))
+            out.append(("deliver", p, q if q < p else q + 1))
+    return out

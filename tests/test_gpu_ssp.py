@@ -1,0 +1,100 @@
+"""GPU parity of SF application under BSP / SSP / ASP: P replicas simulated on one GPU
+(paper_1409_5705_amd.ssp_sim, counters of include/sfb_ssp.h) against the oracle's simulation
+(oracle/ssp.py, Eq. (1) of Section 5) on the same seeded scheduling attempts and mini-batches."""
+import numpy as np
+import pytest
+import torch
+
+import sfb_synth as S
+from parity import TOL_F32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sfb():
+    import paper_1409_5705_amd as m
+    m.lib()
+    return m
+
+
+@pytest.fixture(scope="module")
+def ctx(sfb):
+    c = sfb.Context(0)
+    yield c
+    c.close()
+
+
+def _bound(Wref, W0, n_updates, tol):
+    moved = Wref - W0
+    return tol * np.sqrt(np.mean(moved * moved)) + 2 * n_updates * np.spacing(np.float32(np.max(np.abs(Wref))))
+
+
+@pytest.mark.parametrize("P,s", [(4, 0), (4, 2), (3, -1), (1, 0)])
+def test_replica_trajectories(ctx, sfb, oracle, P, s):
+    import oracle.ssp as ossp
+    from paper_1409_5705_amd.ssp_sim import SspSimulation
+    print("ssp", P, s, flush=True)
+    J, D, B, T, eta = 96, 160, 24, 6, 0.05
+    W0 = S.normal_matrix(J, D, 0.01, seed=9)
+    batches = {(p, t): S.mlr_batch(J, D, B, seed=100 + p, step=t) for p in range(P) for t in range(T)}
+    dev_batches = {k: (torch.from_numpy(X).to("cuda:0"), torch.from_numpy(y).to("cuda:0")) for k, (X, y) in batches.items()}
+    attempts = S.ssp_attempts(P, 60 * P, seed=30 + P + max(s, -1))
+
+    sim = SspSimulation(ctx, P, s, torch.from_numpy(W0).to("cuda:0"), eta, lambda p, t: dev_batches[(p, t)], T)
+    ora = ossp.SspOracle(P, s, W0, eta, lambda p, t: batches[(p, t)], T)
+    sim.run(attempts)
+    ora.run(attempts)
+    torch.cuda.synchronize()
+    assert sim.trace == ora.trace                      # same events took effect, same order of application
+    if s >= 0:
+        assert sim.clock.sfb_ssp_max_staleness_seen() <= s
+    if s != 0 and P > 1:
+        assert sim.clock.sfb_ssp_max_staleness_seen() >= 2   # the schedule does run workers ahead of their peers
+    n_upd = T * P
+    mid = [w.cpu().numpy() for w in sim.W]
+    for p in range(P):
+        err = np.max(np.abs(mid[p].astype(np.float64) - ora.W[p]))
+        assert err <= _bound(ora.W[p], W0, n_upd, TOL_F32), (p, err)
+    # replicas differ while SF sets are in flight (unless BSP has just completed a round)
+    sim.drain()
+    ora.drain()
+    torch.cuda.synchronize()
+    assert sim.trace == ora.trace
+    assert not sim.sets                                 # every SF set was applied by every peer and dropped
+    fin = [w.cpu().numpy() for w in sim.W]
+    for p in range(P):
+        err = np.max(np.abs(fin[p].astype(np.float64) - ora.W[p]))
+        assert err <= _bound(ora.W[p], W0, n_upd, TOL_F32), (p, err)
+    # Eq. (1) with every update delivered: all replicas hold W0 plus the same set of updates
+    for p in range(1, P):
+        assert np.max(np.abs(ora.W[p] - ora.W[0])) <= 1e-12 * max(1.0, np.max(np.abs(ora.W[0])))
+        assert np.max(np.abs(fin[p].astype(np.float64) - fin[0])) <= 2 * _bound(ora.W[0], W0, n_upd, TOL_F32)
+
+
+def test_bsp_equals_minibatch_sgd_over_all_workers(ctx, sfb, oracle):
+    """s = 0: after every round the replicas equal plain mini-batch SGD on the union of the P batches
+    (the exactness claim of Section 3), computed here directly with the oracle's plain functions."""
+    from paper_1409_5705_amd.ssp_sim import SspSimulation
+    P, J, D, B, T, eta = 3, 64, 128, 16, 4, 0.05
+    W0 = S.normal_matrix(J, D, 0.01, seed=5)
+    batches = {(p, t): S.mlr_batch(J, D, B, seed=200 + p, step=t) for p in range(P) for t in range(T)}
+    dev_batches = {k: (torch.from_numpy(X).to("cuda:0"), torch.from_numpy(y).to("cuda:0")) for k, (X, y) in batches.items()}
+    sim = SspSimulation(ctx, P, 0, torch.from_numpy(W0).to("cuda:0"), eta, lambda p, t: dev_batches[(p, t)], T)
+    Wo = W0.astype(np.float64)
+    for t in range(T):
+        for p in range(P):
+            assert sim.compute(p)
+        assert not sim.clock.sfb_ssp_can_compute(0)        # BSP: the next round needs the deliveries below
+        for p in range(P):
+            for q in range(P):
+                if q != p:
+                    assert sim.deliver(p, q)
+        Xall = np.concatenate([batches[(p, t)][0] for p in range(P)])
+        yall = np.concatenate([batches[(p, t)][1] for p in range(P)])
+        Uo, Vo = oracle.mlr_sf(Wo, Xall, yall)
+        Wo = oracle.apply(Wo, Uo, Vo, eta)
+        torch.cuda.synchronize()
+        for p in range(P):
+            err = np.max(np.abs(sim.W[p].cpu().numpy().astype(np.float64) - Wo))
+            assert err <= _bound(Wo, W0, (t + 1) * P, TOL_F32), (t, p, err)

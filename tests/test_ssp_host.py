@@ -1,0 +1,182 @@
+"""Host tests of the BSP / SSP / ASP counters (include/sfb_ssp.h): no GPU.
+
+The library's counters are driven by seeded attempt sequences and compared, event for event, with
+the oracle's own bookkeeping (oracle/ssp.py, written from Section 4 "SSP-SFB" and Eq. (1) of
+Section 5); the oracle's bookkeeping itself is pinned by the invariants the paper states.
+"""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import sfb_synth as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def sfb():
+    import paper_1409_5705_amd as m
+    m.lib()
+    return m
+
+
+class CountingOracle:
+    """oracle.ssp.SspOracle with the arithmetic switched off: only the rules."""
+
+    def __init__(self, oracle_ssp, P, s, T):
+        self.o = oracle_ssp.SspOracle(P, s, np.zeros((1, 1)), 0.0, None, T)
+        o = self.o
+
+        def compute(p):
+            if not o.may_compute(p):
+                return False
+            for q in range(P):
+                if q != p:
+                    o.max_stale = max(o.max_stale, o.t[p] - o.tau[p][q])
+            o.sets[(p, o.t[p])] = (np.zeros((1, 1)), np.zeros((1, 1)))
+            o.trace.append(("compute", p, o.t[p]))
+            o.t[p] += 1
+            o._apply_ready(p)
+            return True
+        o.compute = compute
+
+
+def drive_library(sfb, P, s, T, attempts):
+    clk = sfb.SspClock(P, s)
+    trace = []
+
+    def apply_ready(p):
+        while True:
+            n = clk.sfb_ssp_pop_apply(p)
+            if n is None:
+                return
+            trace.append(("apply", p, n[0], n[1]))
+
+    for a in attempts:
+        if a[0] == "compute":
+            p = a[1]
+            if clk.sfb_ssp_clock(p) < T and clk.sfb_ssp_can_compute(p):
+                trace.append(("compute", p, clk.sfb_ssp_computed(p)))
+                apply_ready(p)
+        else:
+            p, q = a[1], a[2]
+            if clk.sfb_ssp_arrived(p, q) < clk.sfb_ssp_clock(q):
+                trace.append(("deliver", p, q, clk.sfb_ssp_delivered(p, q)))
+                apply_ready(p)
+    return clk, trace
+
+
+@pytest.mark.parametrize("P,s,seed", [(4, 0, 1), (4, 2, 2), (3, 1, 3), (5, -1, 4), (2, 0, 5), (1, 0, 6), (6, 3, 7)])
+def test_counters_match_oracle_bookkeeping(sfb, oracle, P, s, seed):
+    import oracle.ssp as ossp
+    T = 12
+    attempts = S.ssp_attempts(P, 1500, seed)
+    clk, trace = drive_library(sfb, P, s, T, attempts)
+    co = CountingOracle(ossp, P, s, T)
+    co.o.run(attempts)
+    assert trace == co.o.trace
+    assert clk.sfb_ssp_max_staleness_seen() == co.o.max_stale
+    for p in range(P):
+        assert clk.sfb_ssp_clock(p) == co.o.t[p]
+        for q in range(P):
+            if q != p:
+                assert clk.sfb_ssp_tau(p, q) == co.o.tau[p][q]
+                assert clk.sfb_ssp_arrived(p, q) == co.o.arrived[p][q]
+
+
+@pytest.mark.parametrize("P,s,seed", [(4, 0, 11), (4, 2, 12), (3, 5, 13), (5, -1, 14)])
+def test_oracle_bookkeeping_obeys_the_papers_conditions(oracle, P, s, seed):
+    """Pins of the oracle's rules: what the paper states must hold at every event."""
+    import oracle.ssp as ossp
+    T = 10
+    co = CountingOracle(ossp, P, s, T)
+    o = co.o
+    seen_compute = {p: 0 for p in range(P)}
+    for a in S.ssp_attempts(P, 2000, seed):
+        before_t = list(o.t)
+        before_tau = [list(r) for r in o.tau]
+        if a[0] == "compute":
+            ok = o.compute(a[1])
+            if ok:
+                p = a[1]
+                # the worker was not more than s sets ahead of what it had received (SSP condition)
+                if s >= 0:
+                    assert all(before_t[p] - before_tau[p][q] <= s for q in range(P) if q != p)
+                seen_compute[p] += 1
+            elif before_t[a[1]] < T:
+                # it paused: some peer was more than s behind
+                p = a[1]
+                assert s >= 0 and any(before_t[p] - before_tau[p][q] > s for q in range(P) if q != p)
+        else:
+            o.deliver(a[1], a[2])
+        for p in range(P):
+            for q in range(P):
+                if q == p:
+                    continue
+                assert o.tau[p][q] <= o.arrived[p][q] <= o.t[q]      # only what exists and has arrived
+                assert o.tau[p][q] <= o.t[p]                          # no fast-forward (Eq. (1))
+    if s >= 0:
+        assert o.max_stale <= s
+        # clocks of any two workers differ by at most s + 1 sets
+        assert max(o.t) - min(o.t) <= s + 1
+    # applied sets of one peer are applied in the order they were produced
+    for p in range(P):
+        for q in range(P):
+            ts = [e[3] for e in o.trace if e[0] == "apply" and e[1] == p and e[2] == q]
+            assert ts == list(range(len(ts)))
+    o.drain()
+    assert all(t == T for t in o.t)
+    assert all(o.tau[p][q] == T for p in range(P) for q in range(P) if q != p)
+
+
+def test_bsp_is_lockstep(oracle):
+    """s = 0: a worker computes set c only after applying sets 0..c-1 of every peer."""
+    import oracle.ssp as ossp
+    P, T = 4, 8
+    co = CountingOracle(ossp, P, 0, T)
+    o = co.o
+    for a in S.ssp_attempts(P, 3000, 21):
+        if a[0] == "compute":
+            p = a[1]
+            t_before = o.t[p]
+            if o.compute(p):
+                assert all(sum(1 for e in o.trace if e[0] == "apply" and e[1] == p and e[2] == q) >= t_before
+                           for q in range(P) if q != p)
+        else:
+            o.deliver(a[1], a[2])
+
+
+def test_error_paths(sfb):
+    L = sfb.lib()
+    import ctypes
+    assert L.sfb_ssp_create(None, 2, 0) == sfb.SFB_EINVAL
+    h = ctypes.c_void_p()
+    assert L.sfb_ssp_create(ctypes.byref(h), 0, 0) == sfb.SFB_EINVAL
+    assert L.sfb_ssp_can_compute(None, 0) == sfb.SFB_EINVAL
+    clk = sfb.SspClock(2, 0)
+    with pytest.raises(sfb.SfbError):
+        clk.sfb_ssp_clock(2)
+    with pytest.raises(sfb.SfbError):
+        clk.sfb_ssp_delivered(0, 1)          # worker 1 has produced nothing yet
+    with pytest.raises(sfb.SfbError):
+        clk.sfb_ssp_delivered(0, 0)          # no channel to itself
+    assert clk.sfb_ssp_computed(0) == 0
+    assert not clk.sfb_ssp_can_compute(0)    # BSP: must first receive set 0 of worker 1
+    with pytest.raises(sfb.SfbError):
+        clk.sfb_ssp_computed(0)
+    assert clk.sfb_ssp_delivered(1, 0) == 0
+    assert clk.sfb_ssp_pop_apply(1) is None  # held back: worker 1 has not computed its own set 0
+    assert clk.sfb_ssp_computed(1) == 0
+    assert clk.sfb_ssp_pop_apply(1) == (0, 0)
+    assert clk.sfb_ssp_pop_apply(1) is None
+
+
+def test_header_symbols_exported(sfb):
+    hdr = open(os.path.join(ROOT, "include", "sfb_ssp.h")).read()
+    names = set(re.findall(r"\b(sfb_ssp_[a-z_]+)\s*\(", hdr))
+    assert len(names) >= 10
+    L = sfb.lib()
+    for n in names:
+        assert hasattr(L, n), n
