@@ -73,6 +73,120 @@ def cpu_baseline_mlr(cfg, X, y, seed):
     }
 
 
+def bench_fp32_workload(args):
+    """Secondary bench lines: the fp32 parity configurations (MLR small, MLR with 7 peers' SF
+    blocks, DML, sparse coding), one JSON line each.  A step is the whole path of that model."""
+    import numpy as np
+    import torch
+    import oracle
+    import sfb_synth as S
+    import paper_1409_5705_amd as sfb
+
+    name = args.workload
+    cfg = S.CONFIGS[name]
+    dev = torch.device("cuda", 0)
+    ctx = sfb.Context(0)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    model = cfg["model"]
+    if model == "mlr":
+        J, D, B, eta = cfg["J"], cfg["D"], cfg["B"], cfg["eta"]
+        P = cfg.get("peers", 0)
+        N = B * (P + 1)
+        W0 = S.normal_matrix(J, D, cfg["sigma"], seed=0)
+        X, y = S.mlr_batch(J, D, B, seed=0, step=0)
+        W, Xd, yd = d(W0), d(X), d(y)
+        U = torch.empty((N, J), dtype=torch.float32, device=dev)
+        V = torch.empty((N, D), dtype=torch.float32, device=dev)
+        peers = [S.mlr_peer_sf(J, D, B, seed=0, step=0, peer=q) for q in range(P)]
+        for q, (Uq, Vq) in enumerate(peers):
+            U[B * (q + 1):B * (q + 2)] = d(Uq)
+            V[B * (q + 1):B * (q + 2)] = d(Vq)
+
+        def step():
+            ctx.sfb_compute_sf(sfb.SFB_MLR, W, Xd, Y=yd, U=U[:B], V=V[:B])
+            ctx.sfb_apply(W, U, V, eta)
+
+        def oracle_step():
+            Uo, Vo = oracle.mlr_sf(W0, X, y)
+            oracle.apply(W0, np.concatenate([Uo] + [u for u, _ in peers]), np.concatenate([Vo] + [v for _, v in peers]), eta)
+        flops = 2.0 * B * J * D + 2.0 * N * J * D
+        desc = "%s: MLR fp32 J=%d D=%d local B=%d, N=%d rank-1 terms applied per step" % (name, J, D, B, N)
+    elif model == "dml":
+        J, D, B, eta = cfg["K"], cfg["D"], cfg["B"], cfg["eta"]
+        N = B
+        W0 = S.normal_matrix(J, D, cfg["sigma"], seed=0)
+        X, Y, sim = S.dml_batch(D, B, seed=0)
+        W, Xd, Yd, simd = d(W0), d(X), d(Y), d(sim)
+        U = torch.empty((B, J), dtype=torch.float32, device=dev)
+        V = torch.empty((B, D), dtype=torch.float32, device=dev)
+        na = torch.zeros((1,), dtype=torch.int32, device=dev)
+
+        def step():
+            ctx.sfb_compute_sf(sfb.SFB_DML, W, Xd, Y=Yd, sim=simd, U=U, V=V, n_active=na, margin=cfg["margin"])
+            ctx.sfb_apply(W, U, V, eta)
+
+        def oracle_step():
+            Uo, Vo, _ = oracle.dml_sf(W0, X, Y, sim, margin=cfg["margin"])
+            oracle.apply(W0, Uo, Vo, eta)
+        flops = 4.0 * B * J * D
+        desc = "%s: DML fp32 K=%d D=%d B=N=%d pairs (as stated: every hinge term inactive at this init)" % (name, J, D, B)
+    else:
+        J, D, B, eta = cfg["J"], cfg["D"], cfg["B"], cfg["eta"]
+        N = B
+        W0 = S.sc_dictionary(J, D, seed=0)
+        X = S.sc_batch(D, B, seed=0)
+        W, Xd = d(W0), d(X)
+        U = torch.empty((B, J), dtype=torch.float32, device=dev)
+        V = torch.empty((B, D), dtype=torch.float32, device=dev)
+
+        def step():
+            ctx.sfb_compute_sf(sfb.SFB_SC, W, Xd, U=U, V=V, lam=cfg["lam"], ista_iters=cfg["ista_iters"],
+                               power_iters=cfg["power_iters"])
+            ctx.sfb_apply(W, U, V, -eta)
+            ctx.sfb_prox_rows(W, sfb.SFB_PROX_NORMALIZE)
+
+        def oracle_step():
+            Uo, Vo, _ = oracle.sc_sf(W0, X, cfg["lam"], cfg["ista_iters"], cfg["power_iters"])
+            Wn = oracle.apply(W0, Uo, Vo, -eta)
+            oracle.prox_rows(Wn, oracle.PROX_NORMALIZE)
+        flops = (2 * cfg["ista_iters"] + 1) * 2.0 * B * J * D + 2.0 * B * J * D + cfg["power_iters"] * 4.0 * J * D
+        desc = "%s: sparse coding fp32 J=%d D=%d B=N=%d, %d ISTA + %d power iterations, apply, prox" % (
+            name, J, D, B, cfg["ista_iters"], cfg["power_iters"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.sfb_profile_enable(True)
+    ctx.sfb_profile_collect()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = ctx.sfb_profile_collect()
+    ctx.sfb_profile_enable(False)
+    ms = (t1 - t0) * 1e3 / args.steps
+    kernel_ms = {k: v[1] / args.steps for k, v in prof.items()}       # per step, all launches of a group
+    gpu_ms = sum(kernel_ms.values())
+    out = {
+        "metric": "rank-1 SF updates applied/sec (SF compute + reconstruct/apply)",
+        "value": N / (ms * 1e-3), "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic", "config": {"workload": desc},
+        "kernel_ms_per_step": kernel_ms, "gpu_busy_ms_per_step": gpu_ms,
+        "roofline": {"kernel": "all fp32 MFMA contractions of a step", "bound": "mfma",
+                     "achieved": flops / (gpu_ms * 1e-3) / 1e12, "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops / (gpu_ms * 1e-3) / 1e12 / PEAK_F32_TFLOPS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        oracle_step()
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": N / dt, "unit": "updates/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "one whole step of this workload (%.2f s)" % dt}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -97,8 +211,11 @@ def main():
     import sfb_synth as S
     import paper_1409_5705_amd as sfb
 
+    if args.workload in ("mlr_small", "mlr_peers", "dml", "sc"):
+        bench_fp32_workload(args)
+        return
     if args.workload != "mlr_large_bf16":
-        print("unknown workload %r (bench lines exist for mlr_large_bf16 only)" % args.workload, file=sys.stderr)
+        print("unknown workload %r" % args.workload, file=sys.stderr)
         sys.exit(2)
     cfg = S.CONFIGS[args.workload]
     J, D, B, eta = cfg["J"], cfg["D"], cfg["B"], cfg["eta"]

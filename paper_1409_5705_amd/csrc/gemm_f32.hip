@@ -11,6 +11,12 @@
 //
 // Workgroup: 256 threads = 2x2 wavefronts, tile BT x BT x 32 (BT = 64 or 128),
 // one LDS stage plus a register prefetch of the next k-slice.
+//
+// Shapes with few output tiles and a long k (the residual x - W^T a of sparse
+// coding: 512 x 1024 over k = 4096; the DML projections) are split along k over
+// several workgroups: each writes its partial sums to a scratch buffer and a
+// second kernel adds them in a fixed order and applies the epilogue, so results
+// stay bit-reproducible (no float atomics).
 #include "kernels.h"
 
 namespace sfb {
@@ -44,6 +50,9 @@ struct Params {
     float eta, lambda;
     int vecA, vecB;
     int tiles_n;
+    int split_k;       // > 1: workgroup z of a tile covers k-slices [z * slabs, (z + 1) * slabs) and writes partial[z]
+    int64_t slabs;     // k-slices of BK per split
+    float* partial;    // [split_k][M][N]
 };
 
 // Global -> registers for one operand tile.  `outer` is the strided index
@@ -147,6 +156,7 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(Params p)
     const int64_t tile = blockIdx.x;
     const int64_t m0 = (tile / p.tiles_n) * BT;
     const int64_t n0 = (tile % p.tiles_n) * BT;
+    const int64_t z = blockIdx.y;
 
     floatx16 acc[TM][TM];
 #pragma unroll
@@ -157,12 +167,14 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(Params p)
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
     floatx4 ra[TileGeom<BT>::PER_THREAD], rb[TileGeom<BT>::PER_THREAD];
-    const int64_t nk = (p.K + BK - 1) / BK;
-    if (nk > 0) {
-        fetch_tile<BT, A_KS>(ra, p.A, p.lda, m0, p.M, 0, p.K, p.vecA, tid);
-        fetch_tile<BT, B_KS>(rb, p.B, p.ldb, n0, p.N, 0, p.K, p.vecB, tid);
+    const int64_t nk_all = (p.K + BK - 1) / BK;
+    const int64_t k_first = p.split_k > 1 ? z * p.slabs : 0;
+    const int64_t nk = p.split_k > 1 ? (k_first + p.slabs < nk_all ? k_first + p.slabs : nk_all) : nk_all;
+    if (k_first < nk) {
+        fetch_tile<BT, A_KS>(ra, p.A, p.lda, m0, p.M, k_first * BK, p.K, p.vecA, tid);
+        fetch_tile<BT, B_KS>(rb, p.B, p.ldb, n0, p.N, k_first * BK, p.K, p.vecB, tid);
     }
-    for (int64_t kt = 0; kt < nk; ++kt) {
+    for (int64_t kt = k_first; kt < nk; ++kt) {
         stash_tile<BT, A_KS>(ldsA, ra, tid);
         stash_tile<BT, B_KS>(ldsB, rb, tid);
         __syncthreads();
@@ -198,9 +210,28 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(Params p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int64_t row = m0 + wm0 + a * 32 + 8 * (i / 4) + 4 * g + (i % 4);
-                if (row < p.M && col < p.N) epilogue_elem<EPI>(p, row, col, acc[a][b][i], invL);
+                if (row < p.M && col < p.N) {
+                    if (p.split_k > 1)
+                        p.partial[(z * p.M + row) * p.N + col] = acc[a][b][i];
+                    else
+                        epilogue_elem<EPI>(p, row, col, acc[a][b][i], invL);
+                }
             }
         }
+}
+
+// Sum of the k-splits in index order, then the epilogue.
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(Params p)
+{
+    float invL = 0.f;
+    if (EPI == EPI_SHRINK) invL = 1.0f / p.L_ptr[0];
+    const int64_t total = p.M * p.N, stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
+        float sum = p.partial[i];
+        for (int z = 1; z < p.split_k; ++z) sum += p.partial[z * total + i];
+        epilogue_elem<EPI>(p, i / p.N, i % p.N, sum, invL);
+    }
 }
 
 template <int BT, bool A_KS, bool B_KS, int EPI>
@@ -209,24 +240,60 @@ hipError_t launch_one(Params p, hipStream_t stream)
     const int64_t tm = (p.M + BT - 1) / BT, tn = (p.N + BT - 1) / BT;
     p.tiles_n = (int)tn;
     if (tm * tn > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((gemm_f32_kernel<BT, A_KS, B_KS, EPI>), dim3((unsigned)(tm * tn)), dim3(NT), 0, stream, p);
+    const unsigned gz = p.split_k > 1 ? (unsigned)p.split_k : 1u;
+    hipLaunchKernelGGL((gemm_f32_kernel<BT, A_KS, B_KS, EPI>), dim3((unsigned)(tm * tn), gz), dim3(NT), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.split_k <= 1) return e;
+    int64_t g = (p.M * p.N + 255) / 256;
+    if (g > 4096) g = 4096;
+    hipLaunchKernelGGL((splitk_reduce_kernel<EPI>), dim3((unsigned)g), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 
 template <bool A_KS, bool B_KS, int EPI>
-hipError_t launch_sized(const Params& p, hipStream_t stream)
+hipError_t launch_sized(Params p, hipStream_t stream)
 {
     const int64_t t128 = ((p.M + 127) / 128) * ((p.N + 127) / 128);
-    if (t128 >= 256) return launch_one<128, A_KS, B_KS, EPI>(p, stream);
+    if (t128 >= 256) {
+        p.split_k = 1;
+        return launch_one<128, A_KS, B_KS, EPI>(p, stream);
+    }
     return launch_one<64, A_KS, B_KS, EPI>(p, stream);
 }
 
 }  // namespace
 
+// How many ways a contraction is split along k: only when 64 x 64 tiles leave
+// most CUs idle and every split still gets at least 8 k-slices.
+int gemm_f32_split_k(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 1;
+    const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128);
+    if (t128 >= 256) return 1;
+    const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64), nk = (K + BK - 1) / BK;
+    if (tiles >= 256) return 1;
+    int64_t s = (512 + tiles - 1) / tiles;
+    if (s > nk / 8) s = nk / 8;
+    if (s > 8) s = 8;
+    return s < 2 ? 1 : (int)s;
+}
+
+int64_t gemm_f32_partial_bytes(int64_t M, int64_t N, int64_t K)
+{
+    const int s = gemm_f32_split_k(M, N, K);
+    return s > 1 ? (int64_t)s * M * N * 4 : 0;
+}
+
 hipError_t launch_gemm_f32(const GemmF32Args& a, hipStream_t stream)
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
     Params p;
+    p.split_k = a.partial ? gemm_f32_split_k(a.M, a.N, a.K) : 1;
+    p.partial = a.partial;
+    {
+        const int64_t nk = (a.K + BK - 1) / BK;
+        p.slabs = p.split_k > 1 ? (nk + p.split_k - 1) / p.split_k : nk;
+    }
     p.A = a.A; p.B = a.B; p.C = a.C; p.aux = a.aux; p.L_ptr = a.L_ptr;
     p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc;
     p.M = a.M; p.N = a.N; p.K = a.K;

@@ -34,8 +34,12 @@ struct GemmF32Args {
     const float* aux;    // EPI_RESID / EPI_SHRINK, same leading dimension as C; may alias C
     const float* L_ptr;  // EPI_SHRINK: device scalar
     float lambda;        // EPI_SHRINK
+    float* partial;      // scratch of gemm_f32_partial_bytes(M, N, K) for the k-split, or null (no split)
 };
 hipError_t launch_gemm_f32(const GemmF32Args& a, hipStream_t stream);
+// Scratch a contraction of this shape can use to split its k range over several
+// workgroups (0: it would not be split).  16-byte aligned.
+int64_t gemm_f32_partial_bytes(int64_t M, int64_t N, int64_t K);
 
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel of the large MLR path (fp32 accumulate) and its layout helpers.

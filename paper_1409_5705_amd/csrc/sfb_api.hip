@@ -117,6 +117,13 @@ ScLayout sc_layout(int64_t J, int64_t D)
     return l;
 }
 
+// k-split scratch shared by the two contractions of an ISTA iteration.
+int64_t sc_partial_bytes(int64_t B, int64_t J, int64_t D)
+{
+    const int64_t a = sfb::gemm_f32_partial_bytes(B, D, J), b = sfb::gemm_f32_partial_bytes(B, J, D);
+    return round_up(a > b ? a : b);
+}
+
 int check_batch(int32_t model, int64_t J, int64_t D, const sfb_batch* b)
 {
     if (!b || J <= 0 || D <= 0 || b->B < 0) return SFB_EINVAL;
@@ -233,11 +240,11 @@ int64_t sfb_workspace_bytes(int32_t model, int64_t J, int64_t D, const sfb_batch
         case SFB_MLR:
             if (batch->in_dtype == SFB_BF16)   // logits, aligned copy of X, bf16 copy of W
                 return round_up(B * J * 4) + round_up(B * sfb::bf16_pitch(D) * 2) + sfb_shadow_bytes(J, D);
-            return round_up(B * J * 4);
+            return round_up(B * J * 4) + round_up(sfb::gemm_f32_partial_bytes(B, J, D));   // logits, k-split scratch
         case SFB_DML:
-            return round_up(B * J * 4);  // projections Q[B][K], fp32
+            return round_up(B * J * 4) + round_up(sfb::gemm_f32_partial_bytes(B, J, D));   // projections Q[B][K], k-split scratch
         default:
-            return sc_layout(J, D).total;
+            return sc_layout(J, D).total + sc_partial_bytes(B, J, D);
     }
 }
 
@@ -275,7 +282,8 @@ int sfb_shadow_detach(sfb_ctx* ctx)
 int64_t sfb_apply_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dtype)
 {
     if (J <= 0 || D <= 0 || N < 0 || !valid_dtype(sf_dtype)) return SFB_EINVAL;
-    if (sf_dtype == SFB_F32 || N == 0) return 0;
+    if (N == 0) return 0;
+    if (sf_dtype == SFB_F32) return round_up(sfb::gemm_f32_partial_bytes(J, D, N));   // k-split scratch
     if (J % 8 != 0 || D % 8 != 0) return SFB_EINVAL;
     return round_up(sfb::apply_bf16_workspace_bytes(N, J, D));
 }
@@ -318,6 +326,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
             g.C = Z; g.ldc = J;
             g.M = B; g.N = J; g.K = D;
             g.epilogue = sfb::EPI_STORE;
+            if (sfb::gemm_f32_partial_bytes(B, J, D) > 0) g.partial = reinterpret_cast<float*>(ctx->ws + round_up(B * J * 4));
             SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, st));
             SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, false, B, J, st));
         } else {
@@ -349,6 +358,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
         g.C = Q; g.ldc = J;
         g.M = B; g.N = J; g.K = D;
         g.epilogue = sfb::EPI_STORE;
+        if (sfb::gemm_f32_partial_bytes(B, J, D) > 0) g.partial = reinterpret_cast<float*>(ctx->ws + round_up(B * J * 4));
         SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, st));
         if (n_active) SFB_RUN(KID_FILL, sfb::launch_fill_u32(n_active, 0u, 1, st));
         SFB_RUN(KID_DML_SCALE, sfb::launch_dml_scale(Q, batch->sim, static_cast<float*>(U), n_active, batch->margin, B, J, st));
@@ -360,6 +370,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
     const ScLayout lay = sc_layout(J, D);
     float* scratch = reinterpret_cast<float*>(ctx->ws);
     float* Lp = reinterpret_cast<float*>(ctx->ws + lay.off_L);
+    float* ksplit = sc_partial_bytes(B, J, D) > 0 ? reinterpret_cast<float*>(ctx->ws + lay.total) : nullptr;
     float* A = static_cast<float*>(U);
     float* R = static_cast<float*>(V);
     const float* X = static_cast<const float*>(batch->X);
@@ -377,6 +388,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
             g.M = B; g.N = D; g.K = J;
             g.epilogue = sfb::EPI_RESID;
             g.aux = X;
+            g.partial = ksplit;
             SFB_RUN(KID_GEMM_F32_RESID, sfb::launch_gemm_f32(g, st));
         }
         if (it == batch->ista_iters) break;
@@ -389,6 +401,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
         g.aux = A;
         g.L_ptr = Lp;
         g.lambda = batch->lambda;
+        g.partial = ksplit;
         SFB_RUN(KID_GEMM_F32_SHRINK, sfb::launch_gemm_f32(g, st));
     }
     return SFB_OK;
@@ -413,6 +426,7 @@ int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const
         g.M = J; g.N = D; g.K = N;
         g.epilogue = sfb::EPI_RMW;
         g.eta = eta;
+        if (need > 0) g.partial = reinterpret_cast<float*>(ctx->ws);
         SFB_RUN(KID_GEMM_F32_RMW, sfb::launch_gemm_f32(g, ctx->stream));
         if (ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D)
             SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, ctx->shadow_buf, J, D, ctx->stream));
