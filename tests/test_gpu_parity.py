@@ -184,7 +184,8 @@ def test_mlr_peers_trajectory(ctx, sfb, oracle):
 # ---------------------------------------------------------------------------
 # MLR, bf16 inputs / fp32 W and accumulate
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("J,D,B", [(520, 328, 200), (1000, 2056, 257), (8, 8, 1), (264, 10000, 130)])
+@pytest.mark.parametrize("J,D,B", [(520, 328, 200), (1000, 2056, 257), (8, 8, 1), (264, 10000, 130),
+                                   (40008, 264, 300)])   # last: 314 tiles, more than one per persistent workgroup
 def test_mlr_sf_bf16(ctx, sfb, oracle, J, D, B):
     print("mlr_sf_bf16", J, D, B, flush=True)
     W0 = S.normal_matrix(J, D, 0.02, seed=3)
@@ -196,7 +197,9 @@ def test_mlr_sf_bf16(ctx, sfb, oracle, J, D, B):
     print("  err", rel_err(host(U), Uo), max_rel(host(U), Uo))
 
 
-@pytest.mark.parametrize("N,J,D", [(1024, 520, 328), (100, 1000, 2056), (1, 8, 8), (77, 264, 136), (130, 128, 128)])
+@pytest.mark.parametrize("N,J,D", [(1024, 520, 328), (100, 1000, 2056), (1, 8, 8), (77, 264, 136), (130, 128, 128),
+                                   (100, 4104, 4104),     # 289 tiles: several per persistent workgroup, ragged both ways
+                                   (2100, 264, 520)])     # k longer than the headline's, not a multiple of 64
 def test_apply_bf16(ctx, sfb, oracle, N, J, D):
     print("apply_bf16", N, J, D, flush=True)
     U, V = S.mlr_peer_sf(J, D, N, seed=4, step=0, peer=0, bf16=True)
