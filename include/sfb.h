@@ -146,6 +146,21 @@ int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const
               int64_t N, int32_t sf_dtype, float eta);
 
 /*
+ * The same with one coefficient per factor pair, for updates that are a short
+ * signed sum of outer products ("Low-rank Extensions" of Section 2.1: the
+ * rank-2 update u1 v1^T - u2 v2^T of a restricted Boltzmann machine, the rank-3
+ * BFGS update alpha u u^T - beta (u v^T + v u^T)):
+ *       W[j][d] <- W[j][d] - eta * sum_{i<N} coef[i] * U[i][j] * V[i][d].
+ * coef is a device array of N floats (16-byte aligned).  The coefficient is
+ * folded into a scaled copy of V (fp32: exactly one extra rounding per element;
+ * bf16: c * v is rounded to bf16, which is exact for c = +-1).  Needs the
+ * workspace of sfb_apply_signed_workspace_bytes.
+ */
+int64_t sfb_apply_signed_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dtype);
+int sfb_apply_signed(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const void* V,
+                     const float* coef, int64_t N, int32_t sf_dtype, float eta);
+
+/*
  * Proximal operator of sparse coding's norm constraint (Figure 3, "prox"), on
  * the rows of W (the basis vectors in this library's orientation):
  *   SFB_PROX_PROJECT:   w_j <- w_j / ||w_j||  if ||w_j|| > 1, else unchanged;

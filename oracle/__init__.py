@@ -43,6 +43,8 @@ def _load():
         lib.sfbo_num_threads.restype = ctypes.c_int
         lib.sfbo_apply.argtypes = [dp, dp, dp, i64, i64, i64, ctypes.c_double]
         lib.sfbo_apply.restype = None
+        lib.sfbo_apply_signed.argtypes = [dp, dp, dp, dp, i64, i64, i64, ctypes.c_double]
+        lib.sfbo_apply_signed.restype = None
         lib.sfbo_mlr_sf.argtypes = [dp, dp, ctypes.POINTER(ctypes.c_int32), i64, i64, i64, dp, dp]
         lib.sfbo_mlr_sf.restype = None
         lib.sfbo_dml_sf.argtypes = [dp, dp, dp, ctypes.POINTER(ctypes.c_int8), i64, i64, i64,
@@ -88,6 +90,20 @@ def apply(W, U, V, eta):
     if U.shape != (N, J) or V.shape != (N, D):
         raise ValueError("U must be [N][J] and V [N][D]")
     _load().sfbo_apply(_dp(W), _dp(U), _dp(V), N, J, D, float(eta))
+    return W
+
+
+def apply_signed(W, U, V, coef, eta):
+    """Returns W - eta * sum_i coef_i u_i v_i^T (new fp64 array)."""
+    W = np.array(W, dtype=np.float64, order="C", copy=True)
+    J, D = W.shape
+    U = _f64(U)
+    V = _f64(V)
+    c = _f64(coef)
+    N = U.shape[0]
+    if U.shape != (N, J) or V.shape != (N, D) or c.shape != (N,):
+        raise ValueError("U must be [N][J], V [N][D], coef [N]")
+    _load().sfbo_apply_signed(_dp(W), _dp(U), _dp(V), _dp(c), N, J, D, float(eta))
     return W
 
 

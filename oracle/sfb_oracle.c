@@ -58,6 +58,24 @@ void sfbo_apply(double* W, const double* U, const double* V,
 }
 
 /* ------------------------------------------------------------------ */
+/* Signed low-rank updates ("Low-rank Extensions", Section 2.1): an      */
+/* update that is a short signed sum of outer products, e.g. u1 v1^T -   */
+/* u2 v2^T, is applied as W <- W - eta * sum_i c_i u_i v_i^T with one    */
+/* coefficient per factor pair.                                          */
+/* ------------------------------------------------------------------ */
+void sfbo_apply_signed(double* W, const double* U, const double* V, const double* c,
+                       int64_t N, int64_t J, int64_t D, double eta)
+{
+    for (int64_t j = 0; j < J; ++j)
+        for (int64_t d = 0; d < D; ++d) {
+            double acc = 0.0;
+            for (int64_t i = 0; i < N; ++i)
+                acc += c[i] * U[i * J + j] * V[i * D + d];
+            W[j * D + d] -= eta * acc;
+        }
+}
+
+/* ------------------------------------------------------------------ */
 /* Multiclass logistic regression (Section 1; Figure 2).                */
 /* f_i(z) = -log softmax(z)[y_i] with z = W x_i, so by the chain rule   */
 /* u_i = softmax(z) - onehot(y_i) and v_i = x_i.  The row maximum is    */

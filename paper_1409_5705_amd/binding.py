@@ -79,6 +79,10 @@ def lib():
         L.sfb_compute_sf.restype = ctypes.c_int
         L.sfb_apply.argtypes = [vp, vp, i64, i64, vp, vp, i64, i32, ctypes.c_float]
         L.sfb_apply.restype = ctypes.c_int
+        L.sfb_apply_signed_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.sfb_apply_signed_workspace_bytes.restype = i64
+        L.sfb_apply_signed.argtypes = [vp, vp, i64, i64, vp, vp, vp, i64, i32, ctypes.c_float]
+        L.sfb_apply_signed.restype = ctypes.c_int
         L.sfb_prox_rows.argtypes = [vp, vp, i64, i64, i32]
         L.sfb_prox_rows.restype = ctypes.c_int
         L.sfb_strerror.argtypes = [ctypes.c_int]
@@ -283,6 +287,21 @@ class Context:
         rc = lib().sfb_apply(self._h, _ptr(W, "W", dtype=torch.float32), J, D, _ptr(U, "U", shape=(N, J)),
                              _ptr(V, "V", shape=(N, D)), N, _dtype_code(U), float(eta))
         self._check(rc, "sfb_apply")
+
+    def sfb_apply_signed(self, W, U, V, coef, eta):
+        """Enqueues W -= eta * sum_i coef_i u_i v_i^T (in place); coef: fp32 device tensor [N]."""
+        J, D = W.shape
+        N = U.shape[0]
+        if U.dtype != V.dtype:
+            raise TypeError("U and V must share a dtype")
+        need = lib().sfb_apply_signed_workspace_bytes(J, D, N, _dtype_code(U))
+        if need < 0:
+            raise SfbError(int(need), "sfb_apply_signed_workspace_bytes")
+        self._grow_workspace(int(need))
+        rc = lib().sfb_apply_signed(self._h, _ptr(W, "W", dtype=torch.float32), J, D, _ptr(U, "U", shape=(N, J)),
+                                    _ptr(V, "V", shape=(N, D)), _ptr(coef, "coef", dtype=torch.float32, shape=(N,)),
+                                    N, _dtype_code(U), float(eta))
+        self._check(rc, "sfb_apply_signed")
 
     def sfb_prox_rows(self, W, mode=SFB_PROX_PROJECT):
         J, D = W.shape

@@ -424,9 +424,12 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
 // rows_src..pitch-1 are taken as zero.  cols % 8 == 0, pitch % 64 == 0.
 // 64x64 tiles through LDS, 256 threads, 16-byte global accesses on both sides
 // (8 lanes cover one 128-byte row segment).
+// coef (nullable): source row k is scaled by coef[k] (product in fp32, rounded to
+// bf16 to nearest even).
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ src,
                                                              uint16_t* __restrict__ dst, int64_t rows_src,
-                                                             int64_t cols, int64_t pitch)
+                                                             int64_t cols, int64_t pitch,
+                                                             const float* __restrict__ coef)
 {
     constexpr int LP = 72;   // LDS row pitch in elements: 144 bytes, rows stay 16-byte aligned
     __shared__ __attribute__((aligned(16))) uint16_t tile[64 * LP];
@@ -436,7 +439,17 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __r
         const int id = threadIdx.x + 256 * it, r = id >> 3, cc = (id & 7) * 8;
         const int64_t k = k0 + r, c = c0 + cc;
         u32x4 v = {0u, 0u, 0u, 0u};
-        if (k < rows_src && c < cols) v = *reinterpret_cast<const u32x4*>(src + k * cols + c);
+        if (k < rows_src && c < cols) {
+            v = *reinterpret_cast<const u32x4*>(src + k * cols + c);
+            if (coef) {
+                const float ck = coef[k];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t w = v[e];   // (element first into a scalar, see pack_bf16's callers)
+                    v[e] = pack_bf16(ck * __uint_as_float(w << 16), ck * __uint_as_float(w & 0xffff0000u));
+                }
+            }
+        }
         *reinterpret_cast<u32x4*>(&tile[r * LP + cc]) = v;
     }
     __syncthreads();
@@ -557,17 +570,17 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
 
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D) { return (J + D) * bf16_pitch(N) * 2; }
 
-hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, int64_t N, int64_t J, int64_t D,
-                                       void* workspace, hipStream_t stream)
+hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, const float* coef, int64_t N, int64_t J,
+                                       int64_t D, void* workspace, hipStream_t stream)
 {
     if (N <= 0 || J <= 0 || D <= 0) return hipSuccess;
     const int64_t Np = bf16_pitch(N);
     uint16_t* Ut = static_cast<uint16_t*>(workspace);
     uint16_t* Vt = Ut + J * Np;
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((J + 63) / 64), (unsigned)(Np / 64)), dim3(256), 0,
-                       stream, U, Ut, N, J, Np);
+                       stream, U, Ut, N, J, Np, static_cast<const float*>(nullptr));
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((D + 63) / 64), (unsigned)(Np / 64)), dim3(256), 0,
-                       stream, V, Vt, N, D, Np);
+                       stream, V, Vt, N, D, Np, coef);
     return hipGetLastError();
 }
 

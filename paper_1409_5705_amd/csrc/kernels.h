@@ -57,8 +57,9 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
 // (apply_bf16_workspace_bytes, 256-byte aligned), launch_apply_bf16 consumes them.
 // W_shadow (nullable): bf16 copy of W, refreshed with the new values.
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D);
-hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, int64_t N, int64_t J, int64_t D,
-                                       void* workspace, hipStream_t stream);
+// coef (nullable, device, N floats): V^T is written as bf16(coef[i] * V[i][d]).
+hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, const float* coef, int64_t N, int64_t J,
+                                       int64_t D, void* workspace, hipStream_t stream);
 hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, int64_t N, int64_t J, int64_t D, float eta,
                              const void* workspace, hipStream_t stream);
 // Timing experiments (benchmark sweeps): variant / 100 = debug bits; -1 = normal.
@@ -76,6 +77,8 @@ hipError_t launch_diff(const float* X, const float* Y, float* V, int64_t n, hipS
 // n_active (nullable) must have been zeroed; it is incremented once per active row.
 hipError_t launch_dml_scale(const float* Q, const int8_t* sim, float* U, int32_t* n_active,
                             float margin, int64_t B, int64_t K, hipStream_t stream);
+// Vs[i][d] = coef[i] * V[i][d] (N rows of D).
+hipError_t launch_scale_rows(const float* V, const float* coef, float* Vs, int64_t N, int64_t D, hipStream_t stream);
 // Fill n 32-bit words with `value`.
 hipError_t launch_fill_u32(void* p, uint32_t value, int64_t n, hipStream_t stream);
 // Row projection / normalisation of W[J][D].

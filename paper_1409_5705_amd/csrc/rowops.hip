@@ -142,6 +142,13 @@ __global__ __launch_bounds__(256) void diff_kernel(const float* __restrict__ X, 
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) V[i] = X[i] - Y[i];
 }
 
+__global__ __launch_bounds__(256) void scale_rows_kernel(const float* __restrict__ V, const float* __restrict__ coef,
+                                                         float* __restrict__ Vs, int64_t N, int64_t D)
+{
+    const int64_t total = N * D, stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) Vs[i] = coef[i / D] * V[i];
+}
+
 __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ p, uint32_t value, int64_t n)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
@@ -266,6 +273,13 @@ hipError_t launch_diff(const float* X, const float* Y, float* V, int64_t n, hipS
 {
     if (n <= 0) return hipSuccess;
     hipLaunchKernelGGL(diff_kernel, dim3(grid_for(n)), dim3(256), 0, stream, X, Y, V, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_scale_rows(const float* V, const float* coef, float* Vs, int64_t N, int64_t D, hipStream_t stream)
+{
+    if (N <= 0 || D <= 0) return hipSuccess;
+    hipLaunchKernelGGL(scale_rows_kernel, dim3(grid_for(N * D)), dim3(256), 0, stream, V, coef, Vs, N, D);
     return hipGetLastError();
 }
 

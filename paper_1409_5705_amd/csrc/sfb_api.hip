@@ -26,11 +26,12 @@ enum KernelId : int {
     KID_POWER_ITERATION,
     KID_COPY,
     KID_SHADOW,
+    KID_SCALE_ROWS,
     KID_COUNT
 };
 static const char* const kKernelNames[KID_COUNT] = {
     "mlr_forward_bf16", "apply_bf16", "apply_bf16_transpose", "mlr_softmax", "gemm_f32_store", "gemm_f32_rmw(apply)", "gemm_f32_resid",
-    "gemm_f32_shrink", "diff", "dml_scale", "fill", "prox_rows", "power_iteration", "copy", "shadow_convert"};
+    "gemm_f32_shrink", "diff", "dml_scale", "fill", "prox_rows", "power_iteration", "copy", "shadow_convert", "scale_rows"};
 
 struct ProfSpan {
     hipEvent_t t0, t1;
@@ -407,26 +408,31 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
     return SFB_OK;
 }
 
-int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const void* V, int64_t N,
-              int32_t sf_dtype, float eta)
+// Shared by sfb_apply (coef == nullptr) and sfb_apply_signed.
+static int apply_impl(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const void* V, const float* coef,
+                      int64_t N, int32_t sf_dtype, float eta)
 {
-    if (!ctx || J <= 0 || D <= 0 || N < 0 || !valid_dtype(sf_dtype)) return SFB_EINVAL;
-    if (!W || !aligned16(W)) return SFB_EINVAL;
-    if (N == 0) return SFB_OK;
-    if (!U || !V || !aligned16(U) || !aligned16(V)) return SFB_EINVAL;
-    if (sf_dtype == SFB_BF16 && (J % 8 != 0 || D % 8 != 0)) return SFB_EINVAL;
-    const int64_t need = sfb_apply_workspace_bytes(J, D, N, sf_dtype);
+    const int64_t need = coef ? sfb_apply_signed_workspace_bytes(J, D, N, sf_dtype)
+                              : sfb_apply_workspace_bytes(J, D, N, sf_dtype);
+    if (need < 0) return (int)need;
     if (need > 0 && (!ctx->ws || ctx->ws_bytes < need)) return SFB_ENOWS;
     SFB_TRY(hipSetDevice(ctx->device));
     if (sf_dtype == SFB_F32) {
+        const int64_t part = round_up(sfb::gemm_f32_partial_bytes(J, D, N));
+        const float* Vf = static_cast<const float*>(V);
+        if (coef) {   // scaled copy of V behind the k-split scratch
+            float* Vs = reinterpret_cast<float*>(ctx->ws + part);
+            SFB_RUN(KID_SCALE_ROWS, sfb::launch_scale_rows(Vf, coef, Vs, N, D, ctx->stream));
+            Vf = Vs;
+        }
         sfb::GemmF32Args g = {};  // both factors are strided along the SF index
         g.A = static_cast<const float*>(U); g.lda = J; g.a_kstrided = true;
-        g.B = static_cast<const float*>(V); g.ldb = D; g.b_kstrided = true;
+        g.B = Vf; g.ldb = D; g.b_kstrided = true;
         g.C = W; g.ldc = D;
         g.M = J; g.N = D; g.K = N;
         g.epilogue = sfb::EPI_RMW;
         g.eta = eta;
-        if (need > 0) g.partial = reinterpret_cast<float*>(ctx->ws);
+        if (part > 0) g.partial = reinterpret_cast<float*>(ctx->ws);
         SFB_RUN(KID_GEMM_F32_RMW, sfb::launch_gemm_f32(g, ctx->stream));
         if (ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D)
             SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, ctx->shadow_buf, J, D, ctx->stream));
@@ -435,11 +441,46 @@ int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const
                            ? ctx->shadow_buf
                            : nullptr;
         SFB_RUN(KID_APPLY_TRANSPOSE,
-                sfb::launch_apply_bf16_transpose(static_cast<const uint16_t*>(U), static_cast<const uint16_t*>(V), N, J, D,
-                                                 ctx->ws, ctx->stream));
+                sfb::launch_apply_bf16_transpose(static_cast<const uint16_t*>(U), static_cast<const uint16_t*>(V), coef,
+                                                 N, J, D, ctx->ws, ctx->stream));
         SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, Wb, N, J, D, eta, ctx->ws, ctx->stream));
     }
     return SFB_OK;
+}
+
+static int check_apply_args(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const void* U, const void* V, int64_t N,
+                            int32_t sf_dtype)
+{
+    if (!ctx || J <= 0 || D <= 0 || N < 0 || !valid_dtype(sf_dtype)) return SFB_EINVAL;
+    if (!W || !aligned16(W)) return SFB_EINVAL;
+    if (N == 0) return SFB_OK;
+    if (!U || !V || !aligned16(U) || !aligned16(V)) return SFB_EINVAL;
+    if (sf_dtype == SFB_BF16 && (J % 8 != 0 || D % 8 != 0)) return SFB_EINVAL;
+    return SFB_OK;
+}
+
+int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const void* V, int64_t N,
+              int32_t sf_dtype, float eta)
+{
+    const int rc = check_apply_args(ctx, W, J, D, U, V, N, sf_dtype);
+    if (rc != SFB_OK || N == 0) return rc;
+    return apply_impl(ctx, W, J, D, U, V, nullptr, N, sf_dtype, eta);
+}
+
+int64_t sfb_apply_signed_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dtype)
+{
+    const int64_t base = sfb_apply_workspace_bytes(J, D, N, sf_dtype);
+    if (base < 0 || sf_dtype != SFB_F32) return base;       // bf16: the coefficient goes into the V^T copy
+    return base + round_up(N * D * 4);                       // fp32: scaled copy of V
+}
+
+int sfb_apply_signed(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const void* V, const float* coef,
+                     int64_t N, int32_t sf_dtype, float eta)
+{
+    const int rc = check_apply_args(ctx, W, J, D, U, V, N, sf_dtype);
+    if (rc != SFB_OK || N == 0) return rc;
+    if (!coef || !aligned16(coef)) return SFB_EINVAL;
+    return apply_impl(ctx, W, J, D, U, V, coef, N, sf_dtype, eta);
 }
 
 int sfb_prox_rows(sfb_ctx* ctx, float* W, int64_t J, int64_t D, int32_t mode)

@@ -255,6 +255,48 @@ def test_bf16_rejects_unaligned_shapes(ctx, sfb):
 
 
 # ---------------------------------------------------------------------------
+# Signed low-rank updates (one coefficient per factor pair)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("N,J,D", [(2, 200, 136), (333, 264, 520), (1, 8, 8), (600, 1000, 264)])
+def test_apply_signed_f32(ctx, sfb, oracle, N, J, D):
+    print("apply_signed_f32", N, J, D, flush=True)
+    g = np.random.default_rng([55, N])
+    U = g.standard_normal((N, J), dtype=np.float32)
+    V = g.standard_normal((N, D), dtype=np.float32)
+    c = g.standard_normal(N).astype(np.float32)
+    W0 = S.normal_matrix(J, D, 1.0, seed=5)
+    W = dev(W0)
+    ctx.sfb_apply_signed(W, dev(U), dev(V), dev(c), 0.05)
+    Wo = oracle.apply_signed(W0, U, V, c, 0.05)
+    assert rel_err(host(W) - W0, Wo - W0) <= TOL_F32
+
+
+@pytest.mark.parametrize("N,J,D,unit", [(2, 264, 136, True), (300, 520, 328, True), (300, 520, 328, False),
+                                        (1024, 264, 4104, False)])
+def test_apply_signed_bf16(ctx, sfb, oracle, N, J, D, unit):
+    print("apply_signed_bf16", N, J, D, unit, flush=True)
+    U, V = S.mlr_peer_sf(J, D, N, seed=6, step=0, peer=0, bf16=True)
+    g = np.random.default_rng([56, N])
+    c = (g.integers(0, 2, N) * 2 - 1).astype(np.float32) if unit else g.standard_normal(N).astype(np.float32)
+    W0 = S.normal_matrix(J, D, 1.0, seed=6)
+    W = dev(W0)
+    ctx.sfb_apply_signed(W, dev_bf16(U), dev_bf16(V), dev(c), 0.05)
+    Wo = oracle.apply_signed(W0, U, V, c, 0.05)
+    # +-1 coefficients are exact in bf16: only the summation order differs; otherwise c * v is rounded to bf16
+    assert rel_err(host(W) - W0, Wo - W0) <= (TOL_F32 if unit else TOL_BF16)
+
+
+def test_apply_signed_rejects_bad_arguments(ctx, sfb):
+    W = torch.zeros((16, 16), dtype=torch.float32, device="cuda:0")
+    U = torch.zeros((4, 16), dtype=torch.float32, device="cuda:0")
+    L = sfb.lib()
+    import ctypes
+    rc = L.sfb_apply_signed(ctx._h, W.data_ptr(), 16, 16, U.data_ptr(), U.data_ptr(), None, 4, sfb.SFB_F32,
+                            ctypes.c_float(0.1))
+    assert rc == sfb.SFB_EINVAL                     # no coefficients
+
+
+# ---------------------------------------------------------------------------
 # DML
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("K,D,B,sigma", [

@@ -180,6 +180,35 @@ def test_apply_invariants(oracle):
 # ----------------------------------------------------------------------------
 # 4. MLR closed forms / library reduction
 # ----------------------------------------------------------------------------
+def test_apply_signed_pins(oracle):
+    """Signed low-rank updates ("Low-rank Extensions", Section 2.1) against their closed forms."""
+    g = np.random.default_rng(77)
+    J, D = 7, 5
+    W = g.standard_normal((J, D))
+    # rank-2 update of a restricted Boltzmann machine: u1 v1^T - u2 v2^T
+    u1, u2, v1, v2 = g.standard_normal(J), g.standard_normal(J), g.standard_normal(D), g.standard_normal(D)
+    got = oracle.apply_signed(W, np.stack([u1, u2]), np.stack([v1, v2]), np.array([1.0, -1.0]), 0.3)
+    assert np.allclose(got, W - 0.3 * (np.outer(u1, v1) - np.outer(u2, v2)), rtol=0, atol=1e-14)
+    # rank-3 BFGS update on a square symmetric matrix: alpha u u^T - beta (u v^T + v u^T); stays symmetric
+    n = 6
+    H = g.standard_normal((n, n)); H = H + H.T
+    u, v, alpha, beta = g.standard_normal(n), g.standard_normal(n), 0.7, 0.2
+    got = oracle.apply_signed(H, np.stack([u, u, v]), np.stack([u, v, u]), np.array([alpha, -beta, -beta]), -1.0)
+    want = H + alpha * np.outer(u, u) - beta * (np.outer(u, v) + np.outer(v, u))
+    assert np.allclose(got, want, rtol=0, atol=1e-14)
+    assert np.allclose(got, got.T, rtol=0, atol=1e-14)
+    # all coefficients one: the plain SF sum; general coefficients: linear in them
+    N = 9
+    U, V, c = g.standard_normal((N, J)), g.standard_normal((N, D)), g.standard_normal(N)
+    assert np.allclose(oracle.apply_signed(W, U, V, np.ones(N), 0.1), oracle.apply(W, U, V, 0.1), rtol=0, atol=1e-14)
+    assert np.allclose(oracle.apply_signed(W, U, V, c, 0.1), W - 0.1 * (U.T * c) @ V, rtol=0, atol=1e-13)
+    # a zero coefficient removes its pair; the operands are not transposed by mistake (J != D)
+    c0 = c.copy(); c0[3] = 0.0
+    keep = np.arange(N) != 3
+    assert np.allclose(oracle.apply_signed(W, U, V, c0, 0.1), oracle.apply_signed(W, U[keep], V[keep], c[keep], 0.1),
+                       rtol=0, atol=1e-14)
+
+
 def test_mlr_zero_sum_and_column_sums(oracle):
     g = np.random.default_rng(8)
     J, D, B = 11, 6, 5
