@@ -178,6 +178,28 @@ def bench_fp32_workload(args):
                      "achieved": flops / (gpu_ms * 1e-3) / 1e12, "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / (gpu_ms * 1e-3) / 1e12 / PEAK_F32_TFLOPS, "traffic": None},
     }
+    if args.graph:
+        # the same step captured once into a HIP graph and replayed: removes the launch gaps of the
+        # ~90 dependent kernels of a sparse-coding step (profiling events are off during capture)
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            gctx = sfb.Context(0)
+            ctx_eager = ctx
+            ctx = gctx                      # step() resolves `ctx` at call time
+            step()
+            side.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        out["ms_per_step_graph_replay"] = (time.perf_counter() - t0) * 1e3 / args.steps
+        ctx = ctx_eager
     if not args.no_cpu_baseline:
         t0 = time.perf_counter()
         oracle_step()
@@ -198,6 +220,8 @@ def main():
                     help="also run one plain 1 GiB elementwise copy kernel (reference for HBM byte counters)")
     ap.add_argument("--no-shadow", action="store_true",
                     help="do not attach a bf16 working copy of W (the forward then converts W on every call)")
+    ap.add_argument("--graph", action="store_true",
+                    help="fp32 workloads: also time the step replayed from a captured HIP graph")
     ap.add_argument("--forward-variant", type=int, default=-1)
     ap.add_argument("--apply-variant", type=int, default=-1)
     args = ap.parse_args()
