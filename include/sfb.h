@@ -182,6 +182,9 @@ const char* sfb_version(void);
  * group since the last collect into `out` (at most max_entries entries, *count
  * of them filled; `name` points to static storage) and empties the pool.  It
  * returns SFB_ENOWS if launches were dropped because the pool was full.
+ * Keep it disabled (the default) while the stream is being captured into a HIP
+ * graph: with it disabled every call enqueues kernels and device-to-device
+ * copies only and can be captured and replayed.
  */
 typedef struct {
     const char* name;
