@@ -47,6 +47,12 @@ def _load():
         lib.sfbo_apply_signed.restype = None
         lib.sfbo_mlr_sf.argtypes = [dp, dp, ctypes.POINTER(ctypes.c_int32), i64, i64, i64, dp, dp]
         lib.sfbo_mlr_sf.restype = None
+        ip64 = ctypes.POINTER(ctypes.c_int64)
+        ip32 = ctypes.POINTER(ctypes.c_int32)
+        lib.sfbo_mlr_sf_csr.argtypes = [dp, ip64, ip32, dp, ip32, i64, i64, i64, dp, dp]
+        lib.sfbo_mlr_sf_csr.restype = None
+        lib.sfbo_apply_csr.argtypes = [dp, dp, ip64, ip32, dp, i64, i64, i64, ctypes.c_double]
+        lib.sfbo_apply_csr.restype = None
         lib.sfbo_dml_sf.argtypes = [dp, dp, dp, ctypes.POINTER(ctypes.c_int8), i64, i64, i64,
                                     ctypes.c_double, dp, dp, ctypes.POINTER(ctypes.c_int32), dp]
         lib.sfbo_dml_sf.restype = None
@@ -125,6 +131,59 @@ def mlr_sf(W, X, y, with_loss=False):
     if with_loss:
         return U, X, loss
     return U, X
+
+
+def _csr(indptr, indices, values, rows, cols):
+    """Validated CSR triple: int64 indptr [rows+1], int32 indices and fp64 values [nnz];
+    column indices distinct and in range within every row."""
+    indptr = np.ascontiguousarray(indptr, dtype=np.int64)
+    indices = np.ascontiguousarray(indices, dtype=np.int32)
+    values = _f64(values)
+    if indptr.shape != (rows + 1,) or indptr[0] != 0 or np.any(np.diff(indptr) < 0):
+        raise ValueError("indptr must be [rows+1], start at 0 and not decrease")
+    nnz = int(indptr[-1])
+    if indices.shape != (nnz,) or values.shape != (nnz,):
+        raise ValueError("indices and values must have indptr[-1] entries")
+    if nnz and (indices.min() < 0 or indices.max() >= cols):
+        raise ValueError("column index out of range")
+    for i in range(rows):
+        seg = indices[indptr[i]:indptr[i + 1]]
+        if np.unique(seg).size != seg.size:
+            raise ValueError("duplicate column index in row %d" % i)
+    return indptr, indices, values
+
+
+def mlr_sf_csr(W, indptr, indices, values, y, with_loss=False):
+    """MLR first factors U [B][J] for samples given as CSR rows (non-zeros only)."""
+    W = _f64(W)
+    J, D = W.shape
+    B = len(indptr) - 1
+    indptr, indices, values = _csr(indptr, indices, values, B, D)
+    y = np.ascontiguousarray(y, dtype=np.int32)
+    if y.shape != (B,) or (B and (y.min() < 0 or y.max() >= J)):
+        raise ValueError("labels must be [B] in [0, J)")
+    U = np.empty((B, J), dtype=np.float64)
+    loss = np.empty((B,), dtype=np.float64)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    _load().sfbo_mlr_sf_csr(_dp(W), indptr.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                            indices.ctypes.data_as(i32p), _dp(values), y.ctypes.data_as(i32p),
+                            J, D, B, _dp(U), _dp(loss))
+    return (U, loss) if with_loss else U
+
+
+def apply_csr(W, U, indptr, indices, values, eta):
+    """Returns W - eta * sum_i u_i v_i^T with the v_i given as CSR rows (new fp64 array)."""
+    W = np.array(W, dtype=np.float64, order="C", copy=True)
+    J, D = W.shape
+    U = _f64(U)
+    N = U.shape[0]
+    if U.shape != (N, J):
+        raise ValueError("U must be [N][J]")
+    indptr, indices, values = _csr(indptr, indices, values, N, D)
+    _load().sfbo_apply_csr(_dp(W), _dp(U), indptr.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                           indices.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _dp(values),
+                           N, J, D, float(eta))
+    return W
 
 
 def dml_sf(W, X, Y, sim, margin=1.0, with_loss=False):

@@ -110,6 +110,68 @@ void sfbo_mlr_sf(const double* W, const double* X, const int32_t* y,
 }
 
 /* ------------------------------------------------------------------ */
+/* Sparse data (Section 5, experimental setup: the data are sparse, so   */
+/* the second factors v_i = x_i and the update matrices are sparse, and  */
+/* work is done on the non-zeros only).  Row i of a CSR matrix holds the */
+/* pairs (indices[t], values[t]), indptr[i] <= t < indptr[i+1], with     */
+/* distinct column indices.                                              */
+/*   z_j = sum_t W[j][indices[t]] * values[t]   (then as sfbo_mlr_sf)    */
+/*   W[j][indices[t]] -= eta * sum_i U[i][j] * values[t]  (columns no    */
+/*   v_i touches keep their value bit for bit)                           */
+/* ------------------------------------------------------------------ */
+void sfbo_mlr_sf_csr(const double* W, const int64_t* indptr, const int32_t* indices,
+                     const double* values, const int32_t* y,
+                     int64_t J, int64_t D, int64_t B, double* U, double* loss)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < B; ++i) {
+        double* u = U + i * J;
+        for (int64_t j = 0; j < J; ++j) {
+            double z = 0.0;
+            for (int64_t t = indptr[i]; t < indptr[i + 1]; ++t)
+                z += W[j * D + indices[t]] * values[t];
+            u[j] = z;
+        }
+        double m = u[0];
+        for (int64_t j = 1; j < J; ++j)
+            if (u[j] > m) m = u[j];
+        double zy = u[y[i]];
+        double s = 0.0;
+        for (int64_t j = 0; j < J; ++j)
+            s += exp(u[j] - m);
+        for (int64_t j = 0; j < J; ++j)
+            u[j] = exp(u[j] - m) / s;
+        u[y[i]] -= 1.0;
+        if (loss) loss[i] = m + log(s) - zy;
+    }
+}
+
+void sfbo_apply_csr(double* W, const double* U, const int64_t* indptr, const int32_t* indices,
+                    const double* values, int64_t N, int64_t J, int64_t D, double eta)
+{
+#pragma omp parallel
+    {
+        double* acc = (double*)malloc(sizeof(double) * (size_t)(D > 0 ? D : 1));
+        unsigned char* hit = (unsigned char*)malloc((size_t)(D > 0 ? D : 1));
+#pragma omp for schedule(static)
+        for (int64_t j = 0; j < J; ++j) {
+            for (int64_t d = 0; d < D; ++d) { acc[d] = 0.0; hit[d] = 0; }
+            for (int64_t i = 0; i < N; ++i) {
+                double uij = U[i * J + j];
+                for (int64_t t = indptr[i]; t < indptr[i + 1]; ++t) {
+                    acc[indices[t]] += uij * values[t];
+                    hit[indices[t]] = 1;
+                }
+            }
+            for (int64_t d = 0; d < D; ++d)
+                if (hit[d]) W[j * D + d] -= eta * acc[d];
+        }
+        free(acc);
+        free(hit);
+    }
+}
+
+/* ------------------------------------------------------------------ */
 /* Distance metric learning (Section 2: a_i is the difference of the    */
 /* pair's feature vectors; f_i is quadratic for similar pairs and a     */
 /* hinge for dissimilar pairs; W is the K x D projection).              */

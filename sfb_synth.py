@@ -66,6 +66,25 @@ def mlr_batch(J, D, B, seed, step=0, zero_frac=0.0, bf16=False):
     return X, y
 
 
+def csr_from_dense(X):
+    """(indptr int64 [rows+1], indices int32 [nnz], values [nnz]) of the non-zeros of X,
+    row by row with increasing column index: the same data in the sparse storage format."""
+    X = np.asarray(X)
+    rows, cols = np.nonzero(X)          # row-major order: rows non-decreasing, columns increasing within a row
+    indptr = np.zeros(X.shape[0] + 1, dtype=np.int64)
+    np.cumsum(np.bincount(rows, minlength=X.shape[0]), out=indptr[1:])
+    return indptr, cols.astype(np.int32), np.ascontiguousarray(X[rows, cols])
+
+
+def csr_to_dense(indptr, indices, values, cols):
+    """The dense [rows][cols] array a CSR triple stores (zeros elsewhere)."""
+    rows = len(indptr) - 1
+    X = np.zeros((rows, cols), dtype=np.asarray(values).dtype)
+    for i in range(rows):
+        X[i, indices[indptr[i]:indptr[i + 1]]] = values[indptr[i]:indptr[i + 1]]
+    return X
+
+
 def mlr_peer_sf(J, D, n, seed, step, peer, bf16=False):
     """One simulated peer's SF block, as it would arrive over the wire.
 

@@ -366,3 +366,79 @@ def test_small_step_descends(oracle):
     A, R, _ = oracle.sc_sf(Wd, Xs, lam=0.1, ista_iters=5)
     W2 = oracle.apply(Wd, A, R, -1e-3)       # W += eta U^T V
     assert sc_loss_in_W(W2, Xs, A) < sc_loss_in_W(Wd, Xs, A)
+
+
+# ----------------------------------------------------------------------------
+# Sparse samples / sparse second factors (Section 5: work on the non-zeros only)
+# ----------------------------------------------------------------------------
+def _random_csr(g, rows, cols, density, empty_rows=()):
+    indptr, indices, values = [0], [], []
+    for r in range(rows):
+        k = 0 if r in empty_rows else int(g.binomial(cols, density))
+        c = np.sort(g.choice(cols, size=k, replace=False))
+        indices.extend(c.tolist())
+        values.extend(g.standard_normal(k).tolist())
+        indptr.append(len(indices))
+    return np.array(indptr, np.int64), np.array(indices, np.int32), np.array(values, np.float64)
+
+
+def test_csr_functions_pins(oracle):
+    g = np.random.default_rng(4242)
+    J, D, B = 9, 41, 12
+    W = g.standard_normal((J, D))
+    indptr, indices, values = _random_csr(g, B, D, 0.1, empty_rows=(4,))   # an empty row: its logits are all zero
+    y = g.integers(0, J, size=B).astype(np.int32)
+    X = np.zeros((B, D))
+    for i in range(B):                           # densified by hand, not by the shared helper
+        for t in range(indptr[i], indptr[i + 1]):
+            X[i, indices[t]] = values[t]
+    # (a) the plain definition on the dense matrix, by SciPy/NumPy
+    U, loss = oracle.mlr_sf_csr(W, indptr, indices, values, y, with_loss=True)
+    want = scipy.special.softmax(X @ W.T, axis=1)
+    want[np.arange(B), y] -= 1.0
+    assert np.allclose(U, want, rtol=0, atol=1e-14)
+    assert np.allclose(loss.sum(), mlr_loss(W, X, y), rtol=1e-13)
+    # an empty sample: uniform softmax minus the label
+    e = np.full(J, 1.0 / J); e[y[4]] -= 1.0
+    assert indptr[5] == indptr[4] and np.allclose(U[4], e, rtol=0, atol=1e-15)
+    # (b) zeros add nothing: bit-identical to the dense oracle
+    Ud, _ = oracle.mlr_sf(W, X, y)
+    assert np.array_equal(U, Ud)
+    # (c) apply: pure-Python triple loop over the stored entries
+    N = B
+    Uf = g.standard_normal((N, J))
+    eta = 0.37
+    touched = np.zeros(D, bool)
+    dW = np.zeros((J, D))
+    for i in range(N):
+        for t in range(indptr[i], indptr[i + 1]):
+            touched[indices[t]] = True
+            for j in range(J):
+                dW[j, indices[t]] += Uf[i, j] * values[t]
+    want = W - eta * dW
+    got = oracle.apply_csr(W, Uf, indptr, indices, values, eta)
+    assert np.allclose(got, want, rtol=0, atol=1e-14)
+    assert np.allclose(got, W - eta * Uf.T @ X, rtol=0, atol=1e-13)          # = the dense reconstruction
+    assert np.array_equal(got, oracle.apply(W, Uf, X, eta))                  # zeros add nothing
+    assert not touched.all() and np.array_equal(got[:, ~touched], W[:, ~touched])   # untouched columns: bit for bit
+    # (d) a transposed or shifted index would show: J != D, and a single entry moves a single column
+    one = oracle.apply_csr(W, Uf[:1], np.array([0, 1], np.int64), np.array([7], np.int32), np.array([2.0]), 1.0)
+    diff = W - one
+    assert np.allclose(diff[:, 7], 2.0 * Uf[0], rtol=0, atol=1e-15) and np.count_nonzero(np.delete(diff, 7, axis=1)) == 0
+    # (e) malformed input is refused on the host
+    with pytest.raises(ValueError):
+        oracle.apply_csr(W, Uf[:1], np.array([0, 2], np.int64), np.array([3, 3], np.int32), np.array([1.0, 1.0]), 1.0)
+    with pytest.raises(ValueError):
+        oracle.apply_csr(W, Uf[:1], np.array([0, 1], np.int64), np.array([D], np.int32), np.array([1.0]), 1.0)
+
+
+def test_csr_format_helpers_roundtrip():
+    import sfb_synth
+    X, _ = sfb_synth.mlr_batch(5, 37, 11, seed=3, zero_frac=0.8)
+    indptr, indices, values = sfb_synth.csr_from_dense(X)
+    assert indptr[0] == 0 and indptr[-1] == np.count_nonzero(X) == len(indices) == len(values)
+    for i in range(X.shape[0]):
+        seg = indices[indptr[i]:indptr[i + 1]]
+        assert np.all(np.diff(seg) > 0) and np.array_equal(seg, np.nonzero(X[i])[0])
+        assert np.array_equal(values[indptr[i]:indptr[i + 1]], X[i, seg])
+    assert np.array_equal(sfb_synth.csr_to_dense(indptr, indices, values, X.shape[1]), X)
