@@ -161,6 +161,55 @@ int sfb_apply_signed(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U
                      const float* coef, int64_t N, int32_t sf_dtype, float eta);
 
 /*
+ * Sparse samples and sparse second factors (Section 5, experimental setup: the
+ * data are sparse, hence so are the factors v_i = x_i and the update matrices,
+ * and this is used to cut communication and computation).  A block of rows in
+ * compressed sparse row form, all three arrays in device memory (16-byte
+ * aligned) and owned by the caller:
+ *   indptr  [rows + 1]  indptr[0] = 0, non-decreasing, indptr[rows] = nnz;
+ *   indices [nnz]       column of each stored entry, in [0, cols), strictly
+ *                       increasing within a row;
+ *   values  [nnz]       of `dtype` (fp32, or bf16 as raw 16-bit words).
+ * This is the form in which a sparse factor block is buffered and would be
+ * sent: nnz * (4 + element size) + 8 * (rows + 1) bytes instead of rows * cols
+ * elements.  The two calls below take it as it is; they write the dense,
+ * tile-aligned operands of the contractions straight from it (no dense X or V
+ * in the caller's memory), and the contractions themselves stay dense matrix
+ * products: at some 10 % non-zeros and hundreds of rows every block of an
+ * operand tile holds non-zeros, so there is no tile to skip.
+ *
+ * A stored entry with a column outside [0, cols) or a row range outside
+ * [0, nnz] is ignored (nothing is written out of bounds); rows with repeated
+ * columns give an unspecified one of the repeated values.  sfb_csr_check
+ * verifies the format on the device.
+ */
+typedef struct {
+    const int64_t* indptr;
+    const int32_t* indices;
+    const void* values;
+    int64_t rows, cols, nnz;
+    int32_t dtype; /* sfb_dtype of values */
+} sfb_csr;
+
+/* Counts the violations of the format above into *violations (host memory).
+ * Unlike the other calls this one waits for the stream.  Uses the first 256
+ * bytes of the workspace (SFB_ENOWS if there is none). */
+int sfb_csr_check(sfb_ctx* ctx, const sfb_csr* m, int64_t* violations);
+
+/* sfb_compute_sf(SFB_MLR) for samples given as CSR rows (X->rows = B,
+ * X->cols = D): U [B][J] of X->dtype receives softmax(W x_i) - onehot(y_i);
+ * the second factors are the rows of X themselves.  y: int32 labels [B]. */
+int64_t sfb_mlr_sf_csr_workspace_bytes(int64_t J, int64_t D, int64_t B, int32_t dtype);
+int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb_csr* X, const int32_t* y, void* U);
+
+/* sfb_apply / sfb_apply_signed with the second factors given as CSR rows
+ * (V->rows = N, V->cols = D, U [N][J] of V->dtype; coef may be NULL):
+ *       W[j][d] <- W[j][d] - eta * sum_i coef[i] * U[i][j] * V[i][d]. */
+int64_t sfb_apply_csr_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dtype);
+int sfb_apply_csr(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const sfb_csr* V, const float* coef,
+                  float eta);
+
+/*
  * Proximal operator of sparse coding's norm constraint (Figure 3, "prox"), on
  * the rows of W (the basis vectors in this library's orientation):
  *   SFB_PROX_PROJECT:   w_j <- w_j / ||w_j||  if ||w_j|| > 1, else unchanged;

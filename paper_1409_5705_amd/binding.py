@@ -35,6 +35,18 @@ class sfb_batch(ctypes.Structure):
     ]
 
 
+class sfb_csr(ctypes.Structure):
+    _fields_ = [
+        ("indptr", ctypes.c_void_p),
+        ("indices", ctypes.c_void_p),
+        ("values", ctypes.c_void_p),
+        ("rows", ctypes.c_int64),
+        ("cols", ctypes.c_int64),
+        ("nnz", ctypes.c_int64),
+        ("dtype", ctypes.c_int32),
+    ]
+
+
 class sfb_kernel_time(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char_p), ("launches", ctypes.c_int32), ("total_ms", ctypes.c_float)]
 
@@ -83,6 +95,16 @@ def lib():
         L.sfb_apply_signed_workspace_bytes.restype = i64
         L.sfb_apply_signed.argtypes = [vp, vp, i64, i64, vp, vp, vp, i64, i32, ctypes.c_float]
         L.sfb_apply_signed.restype = ctypes.c_int
+        L.sfb_csr_check.argtypes = [vp, ctypes.POINTER(sfb_csr), ctypes.POINTER(i64)]
+        L.sfb_csr_check.restype = ctypes.c_int
+        L.sfb_mlr_sf_csr_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.sfb_mlr_sf_csr_workspace_bytes.restype = i64
+        L.sfb_mlr_sf_csr.argtypes = [vp, vp, i64, i64, ctypes.POINTER(sfb_csr), vp, vp]
+        L.sfb_mlr_sf_csr.restype = ctypes.c_int
+        L.sfb_apply_csr_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.sfb_apply_csr_workspace_bytes.restype = i64
+        L.sfb_apply_csr.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(sfb_csr), vp, ctypes.c_float]
+        L.sfb_apply_csr.restype = ctypes.c_int
         L.sfb_prox_rows.argtypes = [vp, vp, i64, i64, i32]
         L.sfb_prox_rows.restype = ctypes.c_int
         L.sfb_strerror.argtypes = [ctypes.c_int]
@@ -302,6 +324,60 @@ class Context:
                                     _ptr(V, "V", shape=(N, D)), _ptr(coef, "coef", dtype=torch.float32, shape=(N,)),
                                     N, _dtype_code(U), float(eta))
         self._check(rc, "sfb_apply_signed")
+
+    # -- CSR rows (samples / second factors) ----------------------------------
+    @staticmethod
+    def _csr(indptr, indices, values, cols):
+        """sfb_csr over three device tensors: int64 [rows + 1], int32 [nnz], fp32 or bf16 [nnz]."""
+        m = sfb_csr()
+        rows = indptr.numel() - 1
+        nnz = indices.numel()
+        m.indptr = _ptr(indptr, "indptr", dtype=torch.int64)
+        m.indices = _ptr(indices, "indices", dtype=torch.int32) if nnz else None
+        m.values = _ptr(values, "values", shape=(nnz,)) if nnz else None
+        m.rows, m.cols, m.nnz = rows, cols, nnz
+        m.dtype = _dtype_code(values)
+        return m
+
+    def sfb_csr_check(self, indptr, indices, values, cols) -> int:
+        """Number of format violations (waits for the stream)."""
+        m = self._csr(indptr, indices, values, cols)
+        self._grow_workspace(256)
+        bad = ctypes.c_int64(0)
+        self._check(lib().sfb_csr_check(self._h, ctypes.byref(m), ctypes.byref(bad)), "sfb_csr_check")
+        return int(bad.value)
+
+    def sfb_mlr_sf_csr(self, W, indptr, indices, values, y, U):
+        """Enqueues U = softmax(W x_i) - onehot(y_i) for samples given as CSR rows."""
+        J, D = W.shape
+        m = self._csr(indptr, indices, values, D)
+        B = m.rows
+        need = lib().sfb_mlr_sf_csr_workspace_bytes(J, D, B, m.dtype)
+        if need < 0:
+            raise SfbError(int(need), "sfb_mlr_sf_csr_workspace_bytes")
+        self._grow_workspace(int(need))
+        if _dtype_code(U) != m.dtype:
+            raise TypeError("U and the CSR values must share a dtype")
+        rc = lib().sfb_mlr_sf_csr(self._h, _ptr(W, "W", dtype=torch.float32), J, D, ctypes.byref(m),
+                                  _ptr(y, "y (labels)", dtype=torch.int32, shape=(B,)), _ptr(U, "U", shape=(B, J)))
+        self._check(rc, "sfb_mlr_sf_csr")
+
+    def sfb_apply_csr(self, W, U, indptr, indices, values, eta, coef=None):
+        """Enqueues W -= eta * sum_i coef_i u_i v_i^T with the v_i given as CSR rows (in place)."""
+        J, D = W.shape
+        m = self._csr(indptr, indices, values, D)
+        N = m.rows
+        if _dtype_code(U) != m.dtype:
+            raise TypeError("U and the CSR values must share a dtype")
+        need = lib().sfb_apply_csr_workspace_bytes(J, D, N, m.dtype)
+        if need < 0:
+            raise SfbError(int(need), "sfb_apply_csr_workspace_bytes")
+        self._grow_workspace(int(need))
+        rc = lib().sfb_apply_csr(self._h, _ptr(W, "W", dtype=torch.float32), J, D, _ptr(U, "U", shape=(N, J)),
+                                 ctypes.byref(m),
+                                 _ptr(coef, "coef", dtype=torch.float32, shape=(N,)) if coef is not None else None,
+                                 float(eta))
+        self._check(rc, "sfb_apply_csr")
 
     def sfb_prox_rows(self, W, mode=SFB_PROX_PROJECT):
         J, D = W.shape

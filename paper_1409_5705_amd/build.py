@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsfb.so")
-SOURCES = ["sfb_api.hip", "gemm_f32.hip", "gemm_bf16.hip", "rowops.hip", "ssp.cpp"]
+SOURCES = ["sfb_api.hip", "gemm_f32.hip", "gemm_bf16.hip", "rowops.hip", "sparse.hip", "ssp.cpp"]
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
     # packed-fp32 VALU forms are not trusted on the test machines

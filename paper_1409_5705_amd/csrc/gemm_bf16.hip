@@ -556,10 +556,12 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
 {
     if (B <= 0 || J <= 0) return hipSuccess;
     const int64_t pitch = bf16_pitch(D);
-    hipLaunchKernelGGL((pad_rows_bf16_kernel<uint16_t>), dim3(grid_for(B * (pitch / 8))), dim3(256), 0, stream, X,
-                       X_aligned, B, D, pitch);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (X) {   // null: the caller has already written X_aligned (rows of `pitch` elements, zero padded)
+        hipLaunchKernelGGL((pad_rows_bf16_kernel<uint16_t>), dim3(grid_for(B * (pitch / 8))), dim3(256), 0, stream, X,
+                           X_aligned, B, D, pitch);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     Params p = {};
     p.A = X_aligned; p.lda = pitch; p.M = B;
     p.B = W_shadow; p.ldb = pitch; p.N = J;
@@ -572,6 +574,11 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
 
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D) { return (J + D) * bf16_pitch(N) * 2; }
 
+uint16_t* apply_bf16_vt(void* workspace, int64_t N, int64_t J)
+{
+    return static_cast<uint16_t*>(workspace) + J * bf16_pitch(N);
+}
+
 hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, const float* coef, int64_t N, int64_t J,
                                        int64_t D, void* workspace, hipStream_t stream)
 {
@@ -581,8 +588,9 @@ hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, con
     uint16_t* Vt = Ut + J * Np;
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((J + 63) / 64), (unsigned)(Np / 64)), dim3(256), 0,
                        stream, U, Ut, N, J, Np, static_cast<const float*>(nullptr));
-    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((D + 63) / 64), (unsigned)(Np / 64)), dim3(256), 0,
-                       stream, V, Vt, N, D, Np, coef);
+    if (V)     // null: the caller writes V^T itself (apply_bf16_vt)
+        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((D + 63) / 64), (unsigned)(Np / 64)), dim3(256), 0,
+                           stream, V, Vt, N, D, Np, coef);
     return hipGetLastError();
 }
 

@@ -50,6 +50,7 @@ int64_t bf16_pitch(int64_t cols);
 hipError_t launch_shadow_from_w(const float* W, uint16_t* shadow, int64_t J, int64_t D, hipStream_t stream);
 // Z[b][j] = sum_d X[b][d] * shadow[j][d];  X bf16 [B][D], Z fp32 [B][J].
 // X_aligned: scratch for the aligned copy of X, B * bf16_pitch(D) elements.
+// X == nullptr: X_aligned already holds the samples (rows zero padded to the pitch).
 hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, float* Z, uint16_t* X_aligned,
                                    int64_t B, int64_t J, int64_t D, hipStream_t stream);
 // W[j][d] -= eta * sum_i U[i][j] * V[i][d];  U bf16 [N][J], V bf16 [N][D], W fp32 [J][D].
@@ -58,12 +59,28 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
 // W_shadow (nullable): bf16 copy of W, refreshed with the new values.
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D);
 // coef (nullable, device, N floats): V^T is written as bf16(coef[i] * V[i][d]).
+// V == nullptr: only U^T is written; the caller fills V^T, D rows of
+// bf16_pitch(N) elements at apply_bf16_vt(workspace, N, J), columns N.. zero.
+uint16_t* apply_bf16_vt(void* workspace, int64_t N, int64_t J);
 hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, const float* coef, int64_t N, int64_t J,
                                        int64_t D, void* workspace, hipStream_t stream);
 hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, int64_t N, int64_t J, int64_t D, float eta,
                              const void* workspace, hipStream_t stream);
 // Timing experiments (benchmark sweeps): variant / 100 = debug bits; -1 = normal.
 void set_bf16_variant(int forward_variant, int apply_variant);
+
+// ---------------------------------------------------------------------------
+// CSR rows (indptr int64 [rows + 1], indices int32, values fp32 or bf16).
+// ---------------------------------------------------------------------------
+// dst[r * row_stride + c * col_stride] = value (* coef[r] if coef) for every stored
+// entry (r, c); dst must have been zero-filled.  Entries outside [0, cols) and row
+// ranges outside [0, nnz] are skipped.
+hipError_t launch_csr_scatter(const int64_t* indptr, const int32_t* indices, const void* values, bool bf16,
+                              const float* coef, void* dst, int64_t rows, int64_t cols, int64_t nnz,
+                              int64_t row_stride, int64_t col_stride, hipStream_t stream);
+// Adds the number of format violations to *bad (device, zeroed by the caller).
+hipError_t launch_csr_check(const int64_t* indptr, const int32_t* indices, int64_t rows, int64_t cols, int64_t nnz,
+                            unsigned int* bad, hipStream_t stream);
 
 // ---------------------------------------------------------------------------
 // Row-wise kernels.

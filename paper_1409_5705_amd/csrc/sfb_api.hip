@@ -27,11 +27,13 @@ enum KernelId : int {
     KID_COPY,
     KID_SHADOW,
     KID_SCALE_ROWS,
+    KID_CSR,
     KID_COUNT
 };
 static const char* const kKernelNames[KID_COUNT] = {
     "mlr_forward_bf16", "apply_bf16", "apply_bf16_transpose", "mlr_softmax", "gemm_f32_store", "gemm_f32_rmw(apply)", "gemm_f32_resid",
-    "gemm_f32_shrink", "diff", "dml_scale", "fill", "prox_rows", "power_iteration", "copy", "shadow_convert", "scale_rows"};
+    "gemm_f32_shrink", "diff", "dml_scale", "fill", "prox_rows", "power_iteration", "copy", "shadow_convert", "scale_rows",
+    "csr_to_operand"};
 
 struct ProfSpan {
     hipEvent_t t0, t1;
@@ -481,6 +483,145 @@ int sfb_apply_signed(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U
     if (rc != SFB_OK || N == 0) return rc;
     if (!coef || !aligned16(coef)) return SFB_EINVAL;
     return apply_impl(ctx, W, J, D, U, V, coef, N, sf_dtype, eta);
+}
+
+static int check_csr(const sfb_csr* m, int64_t cols)
+{
+    if (!m || m->rows < 0 || m->cols != cols || m->nnz < 0 || !valid_dtype(m->dtype)) return SFB_EINVAL;
+    if (m->rows > 0 && (!m->indptr || !aligned16(m->indptr))) return SFB_EINVAL;
+    if (m->nnz > 0 && (!m->indices || !m->values || !aligned16(m->indices) || !aligned16(m->values))) return SFB_EINVAL;
+    return SFB_OK;
+}
+
+int sfb_csr_check(sfb_ctx* ctx, const sfb_csr* m, int64_t* violations)
+{
+    if (!ctx || !violations || !m) return SFB_EINVAL;
+    const int rc = check_csr(m, m->cols);
+    if (rc != SFB_OK || m->cols <= 0) return SFB_EINVAL;
+    *violations = 0;
+    if (m->rows == 0) return m->nnz == 0 ? SFB_OK : SFB_EINVAL;
+    if (!ctx->ws || ctx->ws_bytes < ALIGN) return SFB_ENOWS;
+    SFB_TRY(hipSetDevice(ctx->device));
+    unsigned int* bad = reinterpret_cast<unsigned int*>(ctx->ws);
+    SFB_RUN(KID_FILL, sfb::launch_fill_u32(bad, 0u, 1, ctx->stream));
+    SFB_RUN(KID_CSR, sfb::launch_csr_check(m->indptr, m->indices, m->rows, m->cols, m->nnz, bad, ctx->stream));
+    unsigned int host = 0;
+    SFB_TRY(hipMemcpyAsync(&host, bad, sizeof(host), hipMemcpyDeviceToHost, ctx->stream));
+    SFB_TRY(hipStreamSynchronize(ctx->stream));
+    *violations = host;
+    return SFB_OK;
+}
+
+int64_t sfb_mlr_sf_csr_workspace_bytes(int64_t J, int64_t D, int64_t B, int32_t dtype)
+{
+    if (!valid_dtype(dtype)) return SFB_EINVAL;
+    sfb_batch b = {};
+    b.B = B;
+    b.in_dtype = b.sf_dtype = dtype;
+    const int64_t base = sfb_workspace_bytes(SFB_MLR, J, D, &b);
+    if (base < 0 || dtype == SFB_BF16) return base;     // bf16: the aligned copy of X is written from the CSR rows
+    return base + round_up(B * D * 4);                   // fp32: dense X
+}
+
+int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb_csr* X, const int32_t* y, void* U)
+{
+    if (!ctx || J <= 0 || D <= 0) return SFB_EINVAL;
+    int rc = check_csr(X, D);
+    if (rc != SFB_OK) return rc;
+    const int64_t B = X->rows;
+    const bool bf16 = X->dtype == SFB_BF16;
+    if (bf16 && (J % 8 != 0 || D % 8 != 0)) return SFB_EINVAL;
+    if (!W || !aligned16(W)) return SFB_EINVAL;
+    if (B == 0) return SFB_OK;
+    if (!y || !U || !aligned16(U)) return SFB_EINVAL;
+    const bool has_shadow = ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D;
+    int64_t need = sfb_mlr_sf_csr_workspace_bytes(J, D, B, X->dtype);
+    if (need < 0) return (int)need;
+    if (bf16 && has_shadow) need -= sfb_shadow_bytes(J, D);
+    if (!ctx->ws || ctx->ws_bytes < need) return SFB_ENOWS;
+    SFB_TRY(hipSetDevice(ctx->device));
+    hipStream_t st = ctx->stream;
+    float* Z = reinterpret_cast<float*>(ctx->ws);
+    if (!bf16) {
+        const int64_t part = round_up(sfb::gemm_f32_partial_bytes(B, J, D));
+        float* Xd = reinterpret_cast<float*>(ctx->ws + round_up(B * J * 4) + part);
+        SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xd, 0u, B * D, st));
+        SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, false, nullptr, Xd, B, D, X->nnz, D, 1, st));
+        sfb::GemmF32Args g = {};
+        g.A = Xd; g.lda = D; g.a_kstrided = false;
+        g.B = W; g.ldb = D; g.b_kstrided = false;
+        g.C = Z; g.ldc = J;
+        g.M = B; g.N = J; g.K = D;
+        g.epilogue = sfb::EPI_STORE;
+        if (part > 0) g.partial = reinterpret_cast<float*>(ctx->ws + round_up(B * J * 4));
+        SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, st));
+        SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, false, B, J, st));
+        return SFB_OK;
+    }
+    const int64_t pitch = sfb::bf16_pitch(D);
+    uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + round_up(B * J * 4));
+    const uint16_t* Wb = ctx->shadow_buf;
+    if (!has_shadow) {
+        uint16_t* tmp = Xa + round_up(B * pitch * 2) / 2;
+        SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, tmp, J, D, st));
+        Wb = tmp;
+    }
+    SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xa, 0u, B * pitch / 2, st));
+    SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, true, nullptr, Xa, B, D, X->nnz, pitch, 1, st));
+    SFB_RUN(KID_FORWARD_BF16, sfb::launch_mlr_forward_bf16(nullptr, Wb, Z, Xa, B, J, D, st));
+    SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st));
+    return SFB_OK;
+}
+
+int64_t sfb_apply_csr_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dtype)
+{
+    const int64_t base = sfb_apply_workspace_bytes(J, D, N, sf_dtype);
+    if (base < 0 || sf_dtype != SFB_F32) return base;   // bf16: V^T is written from the CSR rows
+    return base + round_up(N * D * 4);                   // fp32: dense V
+}
+
+int sfb_apply_csr(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const sfb_csr* V, const float* coef,
+                  float eta)
+{
+    if (!ctx || J <= 0 || D <= 0) return SFB_EINVAL;
+    const int rc = check_csr(V, D);
+    if (rc != SFB_OK) return rc;
+    const int64_t N = V->rows;
+    if (!W || !aligned16(W)) return SFB_EINVAL;
+    if (N == 0) return SFB_OK;
+    if (!U || !aligned16(U) || (coef && !aligned16(coef))) return SFB_EINVAL;
+    if (V->dtype == SFB_BF16 && (J % 8 != 0 || D % 8 != 0)) return SFB_EINVAL;
+    const int64_t need = sfb_apply_csr_workspace_bytes(J, D, N, V->dtype);
+    if (need < 0) return (int)need;
+    if (need > 0 && (!ctx->ws || ctx->ws_bytes < need)) return SFB_ENOWS;
+    SFB_TRY(hipSetDevice(ctx->device));
+    hipStream_t st = ctx->stream;
+    const bool has_shadow = ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D;
+    if (V->dtype == SFB_F32) {
+        const int64_t part = round_up(sfb::gemm_f32_partial_bytes(J, D, N));
+        float* Vd = reinterpret_cast<float*>(ctx->ws + part);
+        SFB_RUN(KID_FILL, sfb::launch_fill_u32(Vd, 0u, N * D, st));
+        SFB_RUN(KID_CSR, sfb::launch_csr_scatter(V->indptr, V->indices, V->values, false, coef, Vd, N, D, V->nnz, D, 1, st));
+        sfb::GemmF32Args g = {};
+        g.A = static_cast<const float*>(U); g.lda = J; g.a_kstrided = true;
+        g.B = Vd; g.ldb = D; g.b_kstrided = true;
+        g.C = W; g.ldc = D;
+        g.M = J; g.N = D; g.K = N;
+        g.epilogue = sfb::EPI_RMW;
+        g.eta = eta;
+        if (part > 0) g.partial = reinterpret_cast<float*>(ctx->ws);
+        SFB_RUN(KID_GEMM_F32_RMW, sfb::launch_gemm_f32(g, st));
+        if (has_shadow) SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, ctx->shadow_buf, J, D, st));
+        return SFB_OK;
+    }
+    const int64_t Np = sfb::bf16_pitch(N);
+    uint16_t* Vt = sfb::apply_bf16_vt(ctx->ws, N, J);
+    SFB_RUN(KID_FILL, sfb::launch_fill_u32(Vt, 0u, D * Np / 2, st));
+    SFB_RUN(KID_CSR, sfb::launch_csr_scatter(V->indptr, V->indices, V->values, true, coef, Vt, N, D, V->nnz, 1, Np, st));
+    SFB_RUN(KID_APPLY_TRANSPOSE, sfb::launch_apply_bf16_transpose(static_cast<const uint16_t*>(U), nullptr, nullptr, N, J,
+                                                                  D, ctx->ws, st));
+    SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, has_shadow ? ctx->shadow_buf : nullptr, N, J, D, eta, ctx->ws, st));
+    return SFB_OK;
 }
 
 int sfb_prox_rows(sfb_ctx* ctx, float* W, int64_t J, int64_t D, int32_t mode)

@@ -1,0 +1,174 @@
+"""GPU parity of the CSR entry points (sparse samples / sparse second factors)
+against the CPU oracle's loops over the stored non-zeros, and bit-equality with
+the dense entry points on the same data.
+"""
+import numpy as np
+import pytest
+
+import sfb_synth as S
+from parity import TOL_BF16, TOL_F32, rel_err
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sfb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1409_5705_amd as m
+    m.lib()   # raises if the HIP library is missing: no fallback
+    return m
+
+
+@pytest.fixture(scope="module")
+def ctx(sfb):
+    c = sfb.Context(0)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def dev_vals(a, bf16):
+    return dev(S.bf16_bits(a)).view(torch.bfloat16) if bf16 else dev(a.astype(np.float32))
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.float().cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy()
+
+
+def csr_dev(X, bf16):
+    indptr, indices, values = S.csr_from_dense(X)
+    return (indptr, indices, values), (dev(indptr), dev(indices), dev_vals(values, bf16))
+
+
+@pytest.mark.parametrize("J,D,B,bf16,zero_frac", [
+    (64, 128, 32, False, 0.9),
+    (1000, 2048, 256, False, 0.9),
+    (37, 50, 7, False, 0.5),        # nothing aligned
+    (520, 328, 200, True, 0.9),
+    (264, 10000, 130, True, 0.9),   # the headline's feature count
+    (40008, 264, 300, True, 0.97),  # several tiles per workgroup; some samples nearly empty
+])
+def test_mlr_sf_csr(ctx, sfb, oracle, J, D, B, bf16, zero_frac):
+    print("mlr_sf_csr", J, D, B, bf16, flush=True)
+    W0 = S.normal_matrix(J, D, 0.02, seed=5)
+    X, y = S.mlr_batch(J, D, B, seed=5, zero_frac=zero_frac, bf16=bf16)
+    X[B // 2] = 0.0                                            # one sample without any non-zero
+    (indptr, indices, values), (ip, ix, vals) = csr_dev(X, bf16)
+    dt = torch.bfloat16 if bf16 else torch.float32
+    U = torch.empty((B, J), dtype=dt, device="cuda:0")
+    assert ctx.sfb_csr_check(ip, ix, vals, D) == 0
+    ctx.sfb_mlr_sf_csr(dev(W0), ip, ix, vals, dev(y), U)
+    Uo = oracle.mlr_sf_csr(W0, indptr, indices, values, y)
+    err = rel_err(host(U), Uo)
+    print("  err", err, flush=True)
+    assert err <= (TOL_BF16 if bf16 else TOL_F32)
+    # same kernels on the same operand values as the dense entry point: same bits
+    Ud = torch.empty_like(U)
+    ctx.sfb_compute_sf(sfb.SFB_MLR, dev(W0), dev_vals(X, bf16).reshape(B, D), Y=dev(y), U=Ud)
+    assert torch.equal(U, Ud)
+
+
+@pytest.mark.parametrize("N,J,D,bf16,zero_frac,signed", [
+    (32, 64, 128, False, 0.9, False),
+    (2048, 1000, 2048, False, 0.9, False),
+    (7, 37, 50, False, 0.5, True),
+    (1024, 520, 328, True, 0.9, False),
+    (100, 4104, 4104, True, 0.99, False),   # 289 tiles; most columns untouched
+    (2100, 264, 520, True, 0.9, True),
+])
+def test_apply_csr(ctx, sfb, oracle, N, J, D, bf16, zero_frac, signed):
+    print("apply_csr", N, J, D, bf16, signed, flush=True)
+    U, _ = S.mlr_peer_sf(J, D, N, seed=6, step=0, peer=0, bf16=bf16)
+    V, _ = S.mlr_batch(J, D, N, seed=6, step=1, zero_frac=zero_frac, bf16=bf16)
+    V[N // 3] = 0.0
+    (indptr, indices, values), (ip, ix, vals) = csr_dev(V, bf16)
+    coef = None
+    coef_d = None
+    if signed:
+        coef = np.where(np.arange(N) % 3 == 0, -1.0, 1.0).astype(np.float32)
+        coef_d = dev(coef)
+    W0 = S.normal_matrix(J, D, 0.01, seed=6)
+    W = dev(W0)
+    eta = 0.001
+    ctx.sfb_apply_csr(W, dev_vals(U, bf16), ip, ix, vals, eta, coef=coef_d)
+    Ueff = U if coef is None else U * coef[:, None]            # exact for +-1
+    ref = oracle.apply_csr(W0, Ueff, indptr, indices, values, eta)
+    got = host(W)
+    step_err = rel_err(got - W0, ref - W0)
+    print("  update err", step_err, flush=True)
+    assert step_err <= TOL_F32 * 4                              # the update itself (difference of close numbers)
+    assert rel_err(got, ref) <= TOL_F32
+    # columns no factor touches keep their bits
+    touched = np.zeros(D, bool)
+    touched[indices] = True
+    assert np.array_equal(got[:, ~touched], W0[:, ~touched])
+    # and the dense entry points give the same bits
+    Wd = dev(W0)
+    if signed:
+        ctx.sfb_apply_signed(Wd, dev_vals(U, bf16), dev_vals(V, bf16).reshape(N, D), coef_d, eta)
+    else:
+        ctx.sfb_apply(Wd, dev_vals(U, bf16), dev_vals(V, bf16).reshape(N, D), eta)
+    assert torch.equal(W, Wd)
+
+
+def test_csr_shadow_copy_stays_current(sfb, oracle):
+    """CSR calls keep an attached bf16 working copy of W current, like the dense ones."""
+    J, D, B, eta = 520, 328, 200, 0.05
+    W0 = S.normal_matrix(J, D, 0.05, seed=22)
+    ca, cb = sfb.Context(0), sfb.Context(0)
+    Wa, Wb = dev(W0), dev(W0)
+    ca.sfb_shadow_attach(Wa)
+    Ua = torch.empty((B, J), dtype=torch.bfloat16, device="cuda:0"); Ub = torch.empty_like(Ua)
+    for step in range(3):
+        X, y = S.mlr_batch(J, D, B, seed=22, step=step, zero_frac=0.9, bf16=True)
+        _, (ip, ix, vals) = csr_dev(X, True)
+        ca.sfb_mlr_sf_csr(Wa, ip, ix, vals, dev(y), Ua)
+        cb.sfb_mlr_sf_csr(Wb, ip, ix, vals, dev(y), Ub)
+        assert torch.equal(Ua, Ub), step
+        ca.sfb_apply_csr(Wa, Ua, ip, ix, vals, eta); cb.sfb_apply_csr(Wb, Ub, ip, ix, vals, eta)
+        assert torch.equal(Wa, Wb)
+    ca.close(); cb.close()
+
+
+def test_csr_edge_cases_and_check(ctx, sfb):
+    J, D = 16, 24
+    W = torch.ones((J, D), dtype=torch.float32, device="cuda:0")
+    i64 = lambda a: dev(np.array(a, np.int64))
+    i32 = lambda a: dev(np.array(a, np.int32))
+    f32 = lambda a: dev(np.array(a, np.float32))
+    # no rows: nothing happens
+    U0 = torch.empty((0, J), dtype=torch.float32, device="cuda:0")
+    ctx.sfb_apply_csr(W, U0, i64([0]), i32([]), f32([]), 1.0)
+    # rows without entries: W unchanged
+    U2 = torch.ones((2, J), dtype=torch.float32, device="cuda:0")
+    ctx.sfb_apply_csr(W, U2, i64([0, 0, 0]), i32([]), f32([]), 1.0)
+    torch.cuda.synchronize()
+    assert torch.equal(W, torch.ones_like(W))
+    # format check: good, unsorted, out of range, bad indptr
+    assert ctx.sfb_csr_check(i64([0, 2, 3]), i32([1, 5, 0]), f32([1, 2, 3]), D) == 0
+    assert ctx.sfb_csr_check(i64([0, 2, 3]), i32([5, 1, 0]), f32([1, 2, 3]), D) == 1
+    assert ctx.sfb_csr_check(i64([0, 2, 3]), i32([1, 1, 0]), f32([1, 2, 3]), D) == 1
+    assert ctx.sfb_csr_check(i64([0, 2, 3]), i32([1, D, -1]), f32([1, 2, 3]), D) == 2
+    assert ctx.sfb_csr_check(i64([0, 4, 3]), i32([1, 2, 3]), f32([1, 2, 3]), D) >= 1
+    assert ctx.sfb_csr_check(i64([1, 2, 3]), i32([1, 2, 3]), f32([1, 2, 3]), D) >= 1
+    # entries outside the matrix are dropped, the others applied
+    W = torch.zeros((J, D), dtype=torch.float32, device="cuda:0")
+    ctx.sfb_apply_csr(W, U2, i64([0, 2, 3]), i32([1, D + 7, -1]), f32([1, 2, 3]), -1.0)
+    torch.cuda.synchronize()
+    want = torch.zeros_like(W)
+    want[:, 1] = 1.0
+    assert torch.equal(W, want)
+    # dtype of U must match the values; bf16 shapes must be multiples of 8
+    with pytest.raises(TypeError):
+        ctx.sfb_apply_csr(W, U2.to(torch.bfloat16), i64([0, 0, 0]), i32([]), f32([]), 1.0)
+    Wb = torch.zeros((12, 16), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(sfb.SfbError) as e:
+        ctx.sfb_apply_csr(Wb, torch.zeros((1, 12), dtype=torch.bfloat16, device="cuda:0"), i64([0, 1]), i32([3]),
+                          f32([1]).to(torch.bfloat16), 1.0)
+    assert e.value.code == sfb.SFB_EINVAL
