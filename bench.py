@@ -222,6 +222,8 @@ def main():
                     help="do not attach a bf16 working copy of W (the forward then converts W on every call)")
     ap.add_argument("--graph", action="store_true",
                     help="fp32 workloads: also time the step replayed from a captured HIP graph")
+    ap.add_argument("--csr", action="store_true",
+                    help="mlr_large_bf16: hand the samples over as CSR rows (sfb_mlr_sf_csr / sfb_apply_csr)")
     ap.add_argument("--forward-variant", type=int, default=-1)
     ap.add_argument("--apply-variant", type=int, default=-1)
     args = ap.parse_args()
@@ -257,7 +259,12 @@ def main():
         X, y = S.mlr_batch(J, D, B, seed=0, step=s, zero_frac=cfg["zero_frac"], bf16=True)
         if s == 0:
             X0, y0 = X, y
-        Xs.append(torch.from_numpy(S.bf16_bits(X)).to(dev).view(torch.bfloat16))
+        if args.csr:
+            ip, ix, v = S.csr_from_dense(X)
+            Xs.append((torch.from_numpy(ip).to(dev), torch.from_numpy(ix).to(dev),
+                       torch.from_numpy(S.bf16_bits(v)).to(dev).view(torch.bfloat16)))
+        else:
+            Xs.append(torch.from_numpy(S.bf16_bits(X)).to(dev).view(torch.bfloat16))
         ys.append(torch.from_numpy(y).to(dev))
     U = torch.empty((B, J), dtype=torch.bfloat16, device=dev)
     ctx = sfb.Context(0)
@@ -266,6 +273,10 @@ def main():
 
     def step(i):
         Xd, yd = Xs[i % len(Xs)], ys[i % len(ys)]
+        if args.csr:
+            ctx.sfb_mlr_sf_csr(W, Xd[0], Xd[1], Xd[2], yd, U)
+            ctx.sfb_apply_csr(W, U, Xd[0], Xd[1], Xd[2], eta)
+            return
         ctx.sfb_compute_sf(sfb.SFB_MLR, W, Xd, Y=yd, U=U)   # V = X
         ctx.sfb_apply(W, U, Xd, eta)
 
@@ -317,6 +328,8 @@ def main():
                     "hbm_frac": smx_bytes / smx_ms / 1e6 / PEAK_HBM_GBS},
         "apply_transposes": {"ms": tr_ms, "hbm_gbs": tr_bytes / tr_ms / 1e6,
                              "hbm_frac": tr_bytes / tr_ms / 1e6 / PEAK_HBM_GBS},
+        # zero fill + scatter of the aligned X and of V^T from the CSR rows, per step (0 for dense input)
+        "csr_to_operand": {"ms": (prof.get("csr_to_operand", (0, 0.0))[1] + prof.get("fill", (0, 0.0))[1]) / args.steps},
         "apply_gemm": {"ms": app_ms, "tflops": gemm_flops / app_ms / 1e9,
                        "mfma_frac": gemm_flops / app_ms / 1e9 / PEAK_BF16_TFLOPS,
                        "hbm_gbs": app_bytes / app_ms / 1e6, "hbm_frac": app_bytes / app_ms / 1e6 / PEAK_HBM_GBS},
@@ -351,7 +364,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "mlr_large_bf16: MLR J=325000 D=10000 B=N=1024, bf16 X/U/V, fp32 W and accumulate, "
-                               "X ~ N(0,1) with 90% zeros stored dense, eta=0.001",
+                               "X ~ N(0,1) with 90% zeros stored " + ("as CSR rows" if args.csr else "dense") + ", eta=0.001",
                    "J": J, "D": D, "B": B, "rank1_terms_per_step": B},
         "tflops_gemm_stages": 2 * gemm_flops / (ms_per_step * 1e-3) / 1e12,
         "mfma_frac_gemm_stages": 2 * gemm_flops / ((fwd_ms + app_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,

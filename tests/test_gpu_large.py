@@ -102,3 +102,33 @@ def test_large_apply_reconstruction(big, sfb, oracle):
     big["ctx"].sfb_apply(Wz, Ud, big["Xd"], -1.0)
     torch.cuda.synchronize()
     assert float(Wz.abs().max()) == 0.0
+
+
+@pytest.mark.timeout(600)
+def test_large_csr_entry_points_match_dense(big, sfb):
+    """At full size the CSR entry points (samples and second factors as stored non-zeros) give the
+    bits of the dense ones, whose results the two tests above compare with the oracle."""
+    J, D, B = big["J"], big["D"], big["B"]
+    indptr, indices, values = S.csr_from_dense(big["X"])
+    print("large: csr nnz %d (density %.3f)" % (len(indices), len(indices) / (B * D)), flush=True)
+    ip = torch.from_numpy(indptr).to("cuda:0")
+    ix = torch.from_numpy(indices).to("cuda:0")
+    vals = torch.from_numpy(S.bf16_bits(values)).to("cuda:0").view(torch.bfloat16)
+    ctx = big["ctx"]
+    assert ctx.sfb_csr_check(ip, ix, vals, D) == 0
+    U = big.get("U")
+    if U is None:
+        U = torch.empty((B, J), dtype=torch.bfloat16, device="cuda:0")
+        ctx.sfb_compute_sf(sfb.SFB_MLR, big["W"], big["Xd"], Y=big["yd"], U=U)
+    U2 = torch.empty_like(U)
+    print("large: mlr_sf_csr", flush=True)
+    ctx.sfb_mlr_sf_csr(big["W"], ip, ix, vals, big["yd"], U2)
+    torch.cuda.synchronize()
+    assert torch.equal(U, U2)
+    Wa = torch.zeros((J, D), dtype=torch.float32, device="cuda:0")
+    Wb = torch.zeros((J, D), dtype=torch.float32, device="cuda:0")
+    print("large: apply dense / csr", flush=True)
+    ctx.sfb_apply(Wa, U, big["Xd"], 1.0)
+    ctx.sfb_apply_csr(Wb, U, ip, ix, vals, 1.0)
+    torch.cuda.synchronize()
+    assert torch.equal(Wa, Wb)
