@@ -210,6 +210,34 @@ int sfb_apply_csr(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, c
                   float eta);
 
 /*
+ * Stochastic dual coordinate ascent for l2-regularised multiclass logistic
+ * regression (Section 2.1, "Stochastic DCA"; the L2-MLR model of Section 5):
+ *   (P)  min_W (1/N) sum_i f_i(W a_i) + (lambda/2) ||W||_F^2,  f_i the logistic loss,
+ *   (D)  min_U (1/N) sum_i f_i^*(-u_i) + h^*(Z),  Z = (1/N) U A^T,  W = grad h^*(Z) = Z / lambda.
+ * The dual variable of a sample is held as the simplex point p_i = onehot(y_i) - u_i
+ * (start: u_i = 0, i.e. p_i = onehot(y_i)); f_i^*(-u_i) is the negative entropy of p_i.
+ *
+ * sfb_sdca_mlr_sf computes, for a mini-batch and all at the same W, each sample's
+ * coordinate step du_i = u_i - argmin_u (D): with z = W a_i, c = ||a_i||^2 / (lambda N),
+ *       log p_j + c p_j = z_j + c P[i][j] - nu   for every class j,   sum_j p_j = 1
+ * (solved to fp32 accuracy), then  dU[i] = beta (p - P[i])  and  P[i] += dU[i].
+ * (dU[i], a_i) is the sufficient-factor pair of the step: the caller applies
+ *       Z <- Z - (1/N) sum_i dU[i] a_i^T     as sfb_apply(Z, dU, X, eta = 1/N)
+ * over its own and its peers' pairs, and then W <- grad h^*(Z) with
+ * sfb_dual_to_primal_l2 (or, equivalently for this h, applies the pairs to W
+ * directly with eta = 1 / (lambda N)).  The 1/N, which the text leaves out of the
+ * update of Z, is what keeps Z = (1/N) U A^T.  beta in (0, 1] scales all steps of a
+ * mini-batch (1 = the sequential algorithm when B = 1); P stays in the simplex.
+ * X [B][D], P [B][J], dU [B][J], W [J][D] fp32 device arrays; N = samples in (P).
+ * Needs the workspace of sfb_sdca_workspace_bytes.
+ */
+int64_t sfb_sdca_workspace_bytes(int64_t J, int64_t D, int64_t B);
+int sfb_sdca_mlr_sf(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const float* X, int64_t B, float* P,
+                    float lambda, int64_t N, float beta, float* dU);
+/* W[j][d] = Z[j][d] / lambda (W may be Z itself).  Keeps an attached bf16 copy of W current. */
+int sfb_dual_to_primal_l2(sfb_ctx* ctx, const float* Z, float* W, int64_t J, int64_t D, float lambda);
+
+/*
  * Proximal operator of sparse coding's norm constraint (Figure 3, "prox"), on
  * the rows of W (the basis vectors in this library's orientation):
  *   SFB_PROX_PROJECT:   w_j <- w_j / ||w_j||  if ||w_j|| > 1, else unchanged;

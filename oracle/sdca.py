@@ -43,17 +43,26 @@ def dual_to_primal_l2(Z, lam):
 
 
 def _solve_class_equations(t, c):
-    """p_j > 0 with log p_j + c p_j = t_j (vector t), by bisection in log p."""
-    # log p + c p is increasing in p; p <= exp(t) and p >= exp(t - c exp(t)).
-    hi = t.copy()
-    lo = t - c * np.exp(t)
-    for _ in range(200):
+    """p_j > 0 with log p_j + c p_j = t_j (vector t), by bisection in x = log p."""
+    # g(x) = x + c exp(x) is increasing; g(t) >= t, and the lower end is moved down until g <= t.
+    hi = np.array(t, dtype=np.float64)
+    width = np.ones_like(hi)
+    lo = hi - width
+    while True:
+        above = lo + c * np.exp(lo) > t
+        if not np.any(above):
+            break
+        width = np.where(above, 2.0 * width, width)
+        lo = np.where(above, hi - width, lo)
+    for _ in range(2000):
         mid = 0.5 * (lo + hi)
         big = mid + c * np.exp(mid) > t
         hi = np.where(big, mid, hi)
         lo = np.where(big, lo, mid)
         if np.max(hi - lo) <= 1e-15 * max(1.0, float(np.max(np.abs(hi)))):
             break
+    else:
+        raise RuntimeError("bisection did not converge")
     return np.exp(0.5 * (lo + hi))
 
 
@@ -65,7 +74,7 @@ def coordinate_minimiser(z, p_old, c):
     if c == 0.0:
         return np.exp(theta - lse)
     lo, hi = lse - c, lse                      # sum p >= 1 at lo, <= 1 at hi
-    for _ in range(200):
+    for _ in range(2000):
         nu = 0.5 * (lo + hi)
         s = float(np.sum(_solve_class_equations(theta - nu, c)))
         if s > 1.0:
@@ -74,6 +83,8 @@ def coordinate_minimiser(z, p_old, c):
             hi = nu
         if hi - lo <= 1e-15 * max(1.0, abs(hi)):
             break
+    else:
+        raise RuntimeError("bisection did not converge")
     return _solve_class_equations(theta - 0.5 * (lo + hi), c)
 
 

@@ -105,6 +105,12 @@ def lib():
         L.sfb_apply_csr_workspace_bytes.restype = i64
         L.sfb_apply_csr.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(sfb_csr), vp, ctypes.c_float]
         L.sfb_apply_csr.restype = ctypes.c_int
+        L.sfb_sdca_workspace_bytes.argtypes = [i64, i64, i64]
+        L.sfb_sdca_workspace_bytes.restype = i64
+        L.sfb_sdca_mlr_sf.argtypes = [vp, vp, i64, i64, vp, i64, vp, ctypes.c_float, i64, ctypes.c_float, vp]
+        L.sfb_sdca_mlr_sf.restype = ctypes.c_int
+        L.sfb_dual_to_primal_l2.argtypes = [vp, vp, vp, i64, i64, ctypes.c_float]
+        L.sfb_dual_to_primal_l2.restype = ctypes.c_int
         L.sfb_prox_rows.argtypes = [vp, vp, i64, i64, i32]
         L.sfb_prox_rows.restype = ctypes.c_int
         L.sfb_strerror.argtypes = [ctypes.c_int]
@@ -378,6 +384,28 @@ class Context:
                                  _ptr(coef, "coef", dtype=torch.float32, shape=(N,)) if coef is not None else None,
                                  float(eta))
         self._check(rc, "sfb_apply_csr")
+
+    # -- SDCA on l2-regularised multiclass logistic regression ---------------
+    def sfb_sdca_mlr_sf(self, W, X, P, lam, N, beta, dU):
+        """Enqueues the dual coordinate steps of a mini-batch: dU = beta (p* - P), P += dU (in place)."""
+        J, D = W.shape
+        B = X.shape[0]
+        need = lib().sfb_sdca_workspace_bytes(J, D, B)
+        if need < 0:
+            raise SfbError(int(need), "sfb_sdca_workspace_bytes")
+        self._grow_workspace(int(need))
+        rc = lib().sfb_sdca_mlr_sf(self._h, _ptr(W, "W", dtype=torch.float32), J, D,
+                                   _ptr(X, "X", dtype=torch.float32, shape=(B, D)), B,
+                                   _ptr(P, "P", dtype=torch.float32, shape=(B, J)), float(lam), int(N), float(beta),
+                                   _ptr(dU, "dU", dtype=torch.float32, shape=(B, J)))
+        self._check(rc, "sfb_sdca_mlr_sf")
+
+    def sfb_dual_to_primal_l2(self, Z, W, lam):
+        """Enqueues W = Z / lam."""
+        J, D = W.shape
+        rc = lib().sfb_dual_to_primal_l2(self._h, _ptr(Z, "Z", dtype=torch.float32, shape=(J, D)),
+                                         _ptr(W, "W", dtype=torch.float32), J, D, float(lam))
+        self._check(rc, "sfb_dual_to_primal_l2")
 
     def sfb_prox_rows(self, W, mode=SFB_PROX_PROJECT):
         J, D = W.shape

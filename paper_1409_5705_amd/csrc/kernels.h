@@ -96,6 +96,13 @@ hipError_t launch_dml_scale(const float* Q, const int8_t* sim, float* U, int32_t
                             float margin, int64_t B, int64_t K, hipStream_t stream);
 // Vs[i][d] = coef[i] * V[i][d] (N rows of D).
 hipError_t launch_scale_rows(const float* V, const float* coef, float* Vs, int64_t N, int64_t D, hipStream_t stream);
+// W[i] = Z[i] / lambda (n elements; W may alias Z).
+hipError_t launch_div_scalar(const float* Z, float* W, float lambda, int64_t n, hipStream_t stream);
+// Dual coordinate steps of l2-regularised multiclass logistic regression at the logits
+// Zl[B][J] = X W^T: P[B][J] (the samples' dual points in the simplex) is advanced by
+// dU = beta (p* - P), p* the coordinate minimiser with c_i = ||x_i||^2 / (lambda n_total).
+hipError_t launch_sdca_mlr(const float* Zl, const float* X, float* P, float* dU, int64_t B, int64_t J, int64_t D,
+                           float lambda, int64_t n_total, float beta, hipStream_t stream);
 // Fill n 32-bit words with `value`.
 hipError_t launch_fill_u32(void* p, uint32_t value, int64_t n, hipStream_t stream);
 // Row projection / normalisation of W[J][D].

@@ -155,6 +155,108 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ p,
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) p[i] = value;
 }
 
+// W = Z / lambda: the primal matrix from the auxiliary one for the squared l2
+// regulariser (W = grad h^*(Z), Section 2.1, Stochastic DCA).
+__global__ __launch_bounds__(256) void div_scalar_kernel(const float* __restrict__ Z, float* __restrict__ W,
+                                                         float lambda, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) W[i] = Z[i] / lambda;
+}
+
+// w > 0 with w + log w = L (w = W0(e^L), the principal Lambert function).  The
+// start is a lower bound of the root (e^L / (1 + e^L) for L < 1, L - log L
+// otherwise), from which Newton's iteration on the concave left side rises
+// monotonically; three steps reach fp32 accuracy over the whole range, four are
+// taken.  Below L = -15 the series w = y - y^2 of y = e^L is exact in fp32.
+__device__ __forceinline__ float lambert_w_exp(float L)
+{
+    if (L < -15.f) {
+        const float y = expf(L);
+        return y - y * y;
+    }
+    float w;
+    if (L >= 1.f) {
+        w = L - __logf(L);
+    } else {
+        const float y = __expf(L);
+        w = y / (1.f + y);
+    }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) w = w * (1.f + L - logf(w)) / (1.f + w);
+    return w;
+}
+
+// Dual coordinate step of l2-regularised multiclass logistic regression, one
+// workgroup per sample.  With z = W a_i (the row of Zl), c = ||a_i||^2 / (lambda N)
+// and the sample's dual point p_old in the simplex, the minimiser p of the dual
+// over this sample's variable solves
+//     log p_j + c p_j = z_j + c p_old_j - nu  (every class j),   sum_j p_j = 1.
+// Each class equation is p_j = W0(c e^{t_j}) / c; sum_j p_j is decreasing in nu
+// and the root lies in [lse(theta) - c, lse(theta)], theta = z + c p_old.  nu is
+// found by Newton's iteration on log(sum p) kept inside that bracket (bisection
+// when a step leaves it).  Outputs: dU = beta (p - p_old), P += dU.
+__global__ __launch_bounds__(256) void sdca_mlr_kernel(const float* __restrict__ Zl, const float* __restrict__ X,
+                                                       float* __restrict__ P, float* __restrict__ dU, int64_t J,
+                                                       int64_t D, float inv_lambda_n, float beta)
+{
+    __shared__ float sm[4];
+    const int64_t i = blockIdx.x;
+    const float* z = Zl + i * J;
+    float* p_old = P + i * J;
+    float* du = dU + i * J;
+    const int tid = threadIdx.x;
+
+    float acc = 0.f;
+    for (int64_t d = tid; d < D; d += 256) {
+        const float x = X[i * D + d];
+        acc += x * x;
+    }
+    const float c = block_sum<256>(acc, sm) * inv_lambda_n;
+
+    float m = -INFINITY;
+    for (int64_t j = tid; j < J; j += 256) m = fmaxf(m, z[j] + c * p_old[j]);
+    m = block_max<256>(m, sm);
+    float s = 0.f;
+    for (int64_t j = tid; j < J; j += 256) s += expf(z[j] + c * p_old[j] - m);
+    s = block_sum<256>(s, sm);
+    const float lse = m + logf(s);
+
+    if (!(c > 1e-30f)) {   // a zero sample: the class equations decouple, p = softmax(z)
+        for (int64_t j = tid; j < J; j += 256) {
+            const float po = p_old[j], d = beta * (expf(z[j] - lse) - po);
+            du[j] = d;
+            p_old[j] = po + d;
+        }
+        return;
+    }
+    const float logc = logf(c), inv_c = 1.f / c;
+    float lo = lse - c, hi = lse, nu = lo;
+    for (int it = 0; it < 32; ++it) {
+        float S = 0.f, T = 0.f;
+        for (int64_t j = tid; j < J; j += 256) {
+            const float w = lambert_w_exp(logc + (z[j] + c * p_old[j] - nu));
+            S += w;                 // c p_j
+            T += w / (1.f + w);     // c p_j / (1 + c p_j)
+        }
+        S = block_sum<256>(S, sm) * inv_c;
+        T = block_sum<256>(T, sm) * inv_c;
+        if (fabsf(S - 1.f) <= 1e-6f) break;          // (every thread holds the same S: a uniform exit)
+        if (S > 1.f) lo = nu; else hi = nu;
+        float cand = nu + S * logf(S) / T;
+        if (!(cand > lo && cand < hi)) cand = 0.5f * (lo + hi);
+        if (cand == nu) break;                        // bracket exhausted at fp32 resolution
+        nu = cand;
+    }
+    for (int64_t j = tid; j < J; j += 256) {
+        const float po = p_old[j];
+        const float p = lambert_w_exp(logc + (z[j] + c * po - nu)) * inv_c;
+        const float d = beta * (p - po);
+        du[j] = d;
+        p_old[j] = po + d;
+    }
+}
+
 // DML: one workgroup per pair.
 __global__ __launch_bounds__(256) void dml_scale_kernel(const float* __restrict__ Q, const int8_t* __restrict__ sim,
                                                         float* __restrict__ U, int32_t* __restrict__ n_active,
@@ -280,6 +382,23 @@ hipError_t launch_scale_rows(const float* V, const float* coef, float* Vs, int64
 {
     if (N <= 0 || D <= 0) return hipSuccess;
     hipLaunchKernelGGL(scale_rows_kernel, dim3(grid_for(N * D)), dim3(256), 0, stream, V, coef, Vs, N, D);
+    return hipGetLastError();
+}
+
+hipError_t launch_div_scalar(const float* Z, float* W, float lambda, int64_t n, hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(div_scalar_kernel, dim3(grid_for(n)), dim3(256), 0, stream, Z, W, lambda, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_sdca_mlr(const float* Zl, const float* X, float* P, float* dU, int64_t B, int64_t J, int64_t D,
+                           float lambda, int64_t n_total, float beta, hipStream_t stream)
+{
+    if (B <= 0 || J <= 0) return hipSuccess;
+    if (B > 0x7fffffffLL) return hipErrorInvalidValue;
+    const float inv_lambda_n = (float)(1.0 / ((double)lambda * (double)n_total));
+    hipLaunchKernelGGL(sdca_mlr_kernel, dim3((unsigned)B), dim3(256), 0, stream, Zl, X, P, dU, J, D, inv_lambda_n, beta);
     return hipGetLastError();
 }
 

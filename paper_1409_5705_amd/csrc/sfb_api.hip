@@ -28,12 +28,14 @@ enum KernelId : int {
     KID_SHADOW,
     KID_SCALE_ROWS,
     KID_CSR,
+    KID_SDCA,
+    KID_DUAL_TO_PRIMAL,
     KID_COUNT
 };
 static const char* const kKernelNames[KID_COUNT] = {
     "mlr_forward_bf16", "apply_bf16", "apply_bf16_transpose", "mlr_softmax", "gemm_f32_store", "gemm_f32_rmw(apply)", "gemm_f32_resid",
     "gemm_f32_shrink", "diff", "dml_scale", "fill", "prox_rows", "power_iteration", "copy", "shadow_convert", "scale_rows",
-    "csr_to_operand"};
+    "csr_to_operand", "sdca_mlr", "dual_to_primal"};
 
 struct ProfSpan {
     hipEvent_t t0, t1;
@@ -621,6 +623,46 @@ int sfb_apply_csr(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, c
     SFB_RUN(KID_APPLY_TRANSPOSE, sfb::launch_apply_bf16_transpose(static_cast<const uint16_t*>(U), nullptr, nullptr, N, J,
                                                                   D, ctx->ws, st));
     SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, has_shadow ? ctx->shadow_buf : nullptr, N, J, D, eta, ctx->ws, st));
+    return SFB_OK;
+}
+
+int64_t sfb_sdca_workspace_bytes(int64_t J, int64_t D, int64_t B)
+{
+    if (J <= 0 || D <= 0 || B < 0) return SFB_EINVAL;
+    return round_up(B * J * 4) + round_up(sfb::gemm_f32_partial_bytes(B, J, D));   // logits, k-split scratch
+}
+
+int sfb_sdca_mlr_sf(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const float* X, int64_t B, float* P,
+                    float lambda, int64_t N, float beta, float* dU)
+{
+    if (!ctx || J <= 0 || D <= 0 || B < 0 || N <= 0) return SFB_EINVAL;
+    if (!(lambda > 0.f) || !(beta > 0.f) || !(beta <= 1.f)) return SFB_EINVAL;
+    if (!W || !aligned16(W)) return SFB_EINVAL;
+    if (B == 0) return SFB_OK;
+    if (!X || !P || !dU || !aligned16(X) || !aligned16(P) || !aligned16(dU)) return SFB_EINVAL;
+    const int64_t need = sfb_sdca_workspace_bytes(J, D, B);
+    if (!ctx->ws || ctx->ws_bytes < need) return SFB_ENOWS;
+    SFB_TRY(hipSetDevice(ctx->device));
+    float* Zl = reinterpret_cast<float*>(ctx->ws);
+    sfb::GemmF32Args g = {};
+    g.A = X; g.lda = D; g.a_kstrided = false;
+    g.B = W; g.ldb = D; g.b_kstrided = false;
+    g.C = Zl; g.ldc = J;
+    g.M = B; g.N = J; g.K = D;
+    g.epilogue = sfb::EPI_STORE;
+    if (sfb::gemm_f32_partial_bytes(B, J, D) > 0) g.partial = reinterpret_cast<float*>(ctx->ws + round_up(B * J * 4));
+    SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, ctx->stream));
+    SFB_RUN(KID_SDCA, sfb::launch_sdca_mlr(Zl, X, P, dU, B, J, D, lambda, N, beta, ctx->stream));
+    return SFB_OK;
+}
+
+int sfb_dual_to_primal_l2(sfb_ctx* ctx, const float* Z, float* W, int64_t J, int64_t D, float lambda)
+{
+    if (!ctx || !Z || !W || J <= 0 || D <= 0 || !(lambda > 0.f)) return SFB_EINVAL;
+    SFB_TRY(hipSetDevice(ctx->device));
+    SFB_RUN(KID_DUAL_TO_PRIMAL, sfb::launch_div_scalar(Z, W, lambda, J * D, ctx->stream));
+    if (ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D)
+        SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, ctx->shadow_buf, J, D, ctx->stream));
     return SFB_OK;
 }
 

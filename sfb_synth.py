@@ -107,6 +107,23 @@ def mlr_peer_sf(J, D, n, seed, step, peer, bf16=False):
     return U, V
 
 
+def sdca_dual_points(J, y, seed, step=0, start_frac=0.25):
+    """Dual points P [B][J] of SDCA on multiclass logistic regression, one simplex point per sample:
+    a fraction still at its start (the one-hot vector of the label, i.e. dual variable zero), the rest
+    somewhere inside the simplex (Dirichlet draws of mixed concentration), as after some epochs."""
+    g = _rng(seed, 6000, step)
+    B = len(y)
+    P = np.empty((B, J), dtype=np.float32)
+    for i in range(B):
+        if g.random() < start_frac:
+            P[i] = 0.0
+            P[i, y[i]] = 1.0
+        else:
+            p = g.dirichlet(np.full(J, g.choice([0.05, 1.0, 20.0])))
+            P[i] = (p / p.sum()).astype(np.float32)
+    return P
+
+
 def dml_batch(D, B, seed, step=0):
     """B pairs: first half similar (y = x + 0.1 N(0,1)), second half dissimilar (y ~ N(0,1))."""
     g = _rng(seed, 4000, step)

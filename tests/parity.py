@@ -29,3 +29,13 @@ def max_rel(got, ref):
     r = np.asarray(ref, dtype=np.float64)
     m = np.max(np.abs(r)) if r.size else 0.0
     return float(np.max(np.abs(g - r)) / (m if m > 0 else 1.0)) if r.size else 0.0
+
+
+def trajectory_check(Wg, Wref, W0, steps, tol):
+    """After `steps` updates from W0: max |g - r| within tol times the rms distance moved, plus the fp32
+    rounding of the stored values themselves."""
+    Wref = np.asarray(Wref)
+    moved = Wref - W0
+    bound = tol * np.sqrt(np.mean(moved * moved)) + 2 * steps * np.spacing(np.float32(np.max(np.abs(Wref))))
+    err = np.max(np.abs(Wg.astype(np.float64) - Wref))
+    assert err <= bound, (err, bound)

@@ -10,6 +10,7 @@ import pytest
 
 import sfb_synth as S
 from parity import TOL_BF16, TOL_F32, max_rel, rel_err
+from parity import trajectory_check as _trajectory_check
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -128,14 +129,6 @@ def test_mlr_large_logits_and_empty_batch(ctx, sfb, oracle):
     assert rel_err(host(U), Uo) <= TOL_F32
     U0 = torch.empty((0, J), dtype=torch.float32, device="cuda:0")
     ctx.sfb_compute_sf(sfb.SFB_MLR, dev(W0), dev(X[:0]), Y=dev(y[:0]), U=U0)   # B = 0
-
-
-def _trajectory_check(Wg, Wref, W0, steps, tol):
-    Wref = np.asarray(Wref)
-    moved = Wref - W0
-    bound = tol * np.sqrt(np.mean(moved * moved)) + 2 * steps * np.spacing(np.float32(np.max(np.abs(Wref))))
-    err = np.max(np.abs(Wg.astype(np.float64) - Wref))
-    assert err <= bound, (err, bound)
 
 
 def test_mlr_small_trajectory(ctx, sfb, oracle):
