@@ -111,6 +111,41 @@ def bench_fp32_workload(args):
             oracle.apply(W0, np.concatenate([Uo] + [u for u, _ in peers]), np.concatenate([Vo] + [v for _, v in peers]), eta)
         flops = 2.0 * B * J * D + 2.0 * N * J * D
         desc = "%s: MLR fp32 J=%d D=%d local B=%d, N=%d rank-1 terms applied per step" % (name, J, D, B, N)
+    elif model == "sdca":
+        from oracle import sdca as osdca
+        J, D, B, lam, Ntot, beta = cfg["J"], cfg["D"], cfg["B"], cfg["lam"], cfg["n_total"], cfg["beta"]
+        P = cfg["peers"]
+        N = B * (P + 1)
+        W0 = S.normal_matrix(J, D, cfg["sigma"], seed=0)
+        Z0 = (W0 * np.float32(lam)).astype(np.float32)
+        X, y = S.mlr_batch(J, D, B, seed=0, step=0)
+        P0 = S.sdca_dual_points(J, y, seed=0)
+        W, Z, Xd = d(W0), d(Z0), d(X)
+        Pd0 = d(P0)
+        Pd = Pd0.clone()
+        U = torch.empty((N, J), dtype=torch.float32, device=dev)
+        V = torch.empty((N, D), dtype=torch.float32, device=dev)
+        V[:B] = Xd
+        # peers' factor blocks: dual steps have the statistics of MLR factors (rows summing to zero), scaled by beta
+        peers = [S.mlr_peer_sf(J, D, B, seed=0, step=0, peer=q) for q in range(P)]
+        for q, (Uq, Vq) in enumerate(peers):
+            U[B * (q + 1):B * (q + 2)] = d(Uq) * beta
+            V[B * (q + 1):B * (q + 2)] = d(Vq)
+
+        def step():
+            Pd.copy_(Pd0)                                     # every timed step starts from the same dual points
+            ctx.sfb_sdca_mlr_sf(W, Xd, Pd, lam, Ntot, beta, U[:B])
+            ctx.sfb_apply(Z, U, V, 1.0 / Ntot)
+            ctx.sfb_dual_to_primal_l2(Z, W, lam)
+
+        def oracle_step():
+            dUo, _ = osdca.sdca_mlr_sf(W0, P0, X, lam, Ntot, beta)
+            Zn = oracle.apply(Z0, np.concatenate([dUo] + [u * beta for u, _ in peers]),
+                              np.concatenate([X] + [v for _, v in peers]), 1.0 / Ntot)
+            osdca.dual_to_primal_l2(Zn, lam)
+        flops = 2.0 * B * J * D + 2.0 * N * J * D
+        desc = "%s: SDCA on l2-regularised MLR fp32 J=%d D=%d local B=%d, N=%d factor pairs applied to Z per step, W = Z/lambda" % (
+            name, J, D, B, N)
     elif model == "dml":
         J, D, B, eta = cfg["K"], cfg["D"], cfg["B"], cfg["eta"]
         N = B
@@ -237,7 +272,7 @@ def main():
     import sfb_synth as S
     import paper_1409_5705_amd as sfb
 
-    if args.workload in ("mlr_small", "mlr_peers", "dml", "sc"):
+    if args.workload in ("mlr_small", "mlr_peers", "dml", "sc", "sdca_peers"):
         bench_fp32_workload(args)
         return
     if args.workload != "mlr_large_bf16":

@@ -20,6 +20,9 @@ CONFIGS = {
     "mlr_peers": dict(model="mlr", J=1000, D=2048, B=256, peers=7, steps=20, eta=0.01, sigma=0.01),
     "mlr_large_bf16": dict(model="mlr", J=325000, D=10000, B=1024, steps=5, eta=0.001, sigma=0.01,
                            zero_frac=0.9, bf16=True),
+    # SDCA on l2-regularised MLR at the shape of mlr_peers: local dual steps + 7 peers' factor blocks
+    "sdca_peers": dict(model="sdca", J=1000, D=2048, B=256, peers=7, steps=20, lam=1e-3, n_total=100000, beta=0.125,
+                       sigma=0.05),
     "dml": dict(model="dml", K=1024, D=4096, B=512, steps=10, eta=1e-4, sigma=0.01, margin=1.0),
     "sc": dict(model="sc", J=4096, D=1024, B=512, steps=5, eta=0.01, lam=0.1,
                ista_iters=20, power_iters=10),
