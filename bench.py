@@ -213,6 +213,8 @@ def bench_fp32_workload(args):
                      "achieved": flops / (gpu_ms * 1e-3) / 1e12, "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / (gpu_ms * 1e-3) / 1e12 / PEAK_F32_TFLOPS, "traffic": None},
     }
+    if args.measured_peaks is not None:
+        out["measured_peaks"] = args.measured_peaks
     if args.graph:
         # the same step captured once into a HIP graph and replayed: removes the launch gaps of the
         # ~90 dependent kernels of a sparse-coding step (profiling events are off during capture)
@@ -257,6 +259,9 @@ def main():
                     help="do not attach a bf16 working copy of W (the forward then converts W on every call)")
     ap.add_argument("--graph", action="store_true",
                     help="fp32 workloads: also time the step replayed from a captured HIP graph")
+    ap.add_argument("--peaks", action="store_true",
+                    help="first run the stand-alone MFMA-only / HBM-streaming probe (paper_1409_5705_amd/sfb_peaks) "
+                         "and report what this GPU sustains next to the published peaks")
     ap.add_argument("--csr", action="store_true",
                     help="mlr_large_bf16: hand the samples over as CSR rows (sfb_mlr_sf_csr / sfb_apply_csr)")
     ap.add_argument("--forward-variant", type=int, default=-1)
@@ -266,6 +271,21 @@ def main():
         print("bench.py measures one GPU: this build has no multi-GPU path (each GPU box has one GPU); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    measured_peaks = None
+    if args.peaks:      # a child process, started before this one touches the GPU
+        import subprocess
+        exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_1409_5705_amd", "sfb_peaks")
+        if not os.path.exists(exe):
+            print("bench: %s is not built (run __graft_entry__.build())" % exe, file=sys.stderr)
+            sys.exit(2)
+        r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+        if r.returncode != 0:
+            print("bench: sfb_peaks failed:\n" + r.stderr, file=sys.stderr)
+            sys.exit(2)
+        measured_peaks = json.loads(r.stdout.strip().splitlines()[-1])
+        log("bench: measured peaks " + json.dumps(measured_peaks))
+    args.measured_peaks = measured_peaks
 
     import numpy as np
     import torch
@@ -406,6 +426,8 @@ def main():
         "stages": stages,
         "roofline": roof,
     }
+    if args.measured_peaks is not None:
+        out["measured_peaks"] = args.measured_peaks
     if not args.no_cpu_baseline:
         log("bench: timing the CPU oracle on a bounded sample")
         out["cpu_baseline"] = cpu_baseline_mlr(cfg, X0, y0, seed=0)

@@ -8,6 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsfb.so")
+PEAKS = os.path.join(HERE, "sfb_peaks")
 SOURCES = ["sfb_api.hip", "gemm_f32.hip", "gemm_bf16.hip", "rowops.hip", "sparse.hip", "ssp.cpp"]
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
@@ -48,6 +49,12 @@ def build_library(verbose: bool = False) -> str:
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
     os.replace(tmp, LIB)
+    # the stand-alone MFMA / HBM probe behind `bench.py --peaks`
+    tmp = PEAKS + ".tmp%d" % os.getpid()
+    r = subprocess.run([hipcc] + FLAGS + ["-o", tmp, os.path.join(CSRC, "peaks.hip")], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for peaks.hip:\n%s\n%s" % (r.stdout, r.stderr))
+    os.replace(tmp, PEAKS)
     return LIB
 
 

@@ -1,0 +1,157 @@
+// Stand-alone probe of what this GPU sustains on the two resources the
+// roofline fractions are quoted against: the MFMA pipes (a register-only loop of
+// bf16 32x32x16 and fp32 32x32x2 MFMAs, one and two wavefronts per SIMD) and HBM
+// (streaming read, copy and read-modify-write of buffers far larger than the
+// caches, 16 bytes per lane).  Prints one JSON object.  Used by `bench.py --peaks`;
+// not part of the library.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+
+#define CK(x)                                                                          \
+    do {                                                                               \
+        hipError_t e_ = (x);                                                           \
+        if (e_ != hipSuccess) {                                                        \
+            fprintf(stderr, "HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); \
+            return 1;                                                                  \
+        }                                                                              \
+    } while (0)
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <bool BF16>
+__global__ __launch_bounds__(512) void mfma_loop(float* out, int iters)
+{
+    floatx16 acc[4];
+    for (int a = 0; a < 4; ++a)
+        for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
+    const float x = 1.0f + threadIdx.x * 1e-6f, y = 0.5f;
+    bf16x8 xb, yb;
+    for (int i = 0; i < 8; ++i) {
+        xb[i] = (__bf16)x;
+        yb[i] = (__bf16)y;
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                if (BF16)
+                    acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xb, yb, acc[a], 0, 0, 0);
+                else
+                    acc[a] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, acc[a], 0, 0, 0);
+            }
+    }
+    float s = 0.f;
+    for (int a = 0; a < 4; ++a)
+        for (int i = 0; i < 16; ++i) s += acc[a][i];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+// MODE 0: read only (sum kept in a register, one store per thread); 1: copy; 2: read-modify-write in place.
+// Four independent 16-byte accesses per lane and iteration.
+template <int MODE>
+__global__ __launch_bounds__(256) void stream_kernel(const floatx4* __restrict__ src, floatx4* __restrict__ dst,
+                                                     size_t n4, float* sink)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n4; i += 4 * stride) {
+        floatx4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (MODE == 0) acc += v[u];
+            if (MODE == 1) __builtin_nontemporal_store(v[u], dst + i + u * stride);
+            if (MODE == 2) __builtin_nontemporal_store(v[u] * 0.999f, dst + i + u * stride);
+        }
+    }
+    for (; i < n4; i += stride) {
+        const floatx4 v = __builtin_nontemporal_load(src + i);
+        if (MODE == 0) acc += v;
+        if (MODE == 1) __builtin_nontemporal_store(v, dst + i);
+        if (MODE == 2) __builtin_nontemporal_store(v * 0.999f, dst + i);
+    }
+    if (MODE == 0) sink[(size_t)blockIdx.x * 256 + threadIdx.x] = acc[0] + acc[1] + acc[2] + acc[3];
+}
+
+template <typename F>
+int time_ms(F launch, int reps, float* ms_out)
+{
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    launch();
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0, 0));
+    for (int r = 0; r < reps; ++r) launch();
+    CK(hipEventRecord(e1, 0));
+    CK(hipGetLastError());
+    CK(hipDeviceSynchronize());
+    CK(hipEventElapsedTime(ms_out, e0, e1));
+    *ms_out /= reps;
+    CK(hipEventDestroy(e0));
+    CK(hipEventDestroy(e1));
+    return 0;
+}
+
+int main()
+{
+    hipDeviceProp_t prop;
+    CK(hipGetDeviceProperties(&prop, 0));
+    const int cus = prop.multiProcessorCount;
+    float* out;
+    CK(hipMalloc(&out, (size_t)cus * 512 * 4));
+    const int iters = 4000;
+    float ms;
+    double tf[4];
+    int k = 0;
+    for (int bf16 = 1; bf16 >= 0; --bf16)
+        for (int threads = 256; threads <= 512; threads += 256) {
+            if (bf16) {
+                if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<true>, dim3(cus), dim3(threads), 0, 0, out, iters); }, 3, &ms))
+                    return 1;
+            } else {
+                if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<false>, dim3(cus), dim3(threads), 0, 0, out, iters); }, 3, &ms))
+                    return 1;
+            }
+            const double mfmas = (double)iters * 32 * (threads / 64) * cus;
+            tf[k++] = mfmas * (bf16 ? 32768.0 : 4096.0) / (ms * 1e-3) / 1e12;
+        }
+    CK(hipFree(out));
+
+    const size_t bytes = (size_t)4 << 30;   // 4 GiB per buffer
+    floatx4 *a, *b;
+    float* sink;
+    CK(hipMalloc(&a, bytes));
+    CK(hipMalloc(&b, bytes));
+    CK(hipMalloc(&sink, (size_t)cus * 32 * 256 * 4));
+    CK(hipMemset(a, 0, bytes));
+    CK(hipMemset(b, 0, bytes));
+    const size_t n4 = bytes / 16;
+    double gbs[3] = {0.0, 0.0, 0.0};
+    for (unsigned per_cu = 4; per_cu <= 32; per_cu *= 2) {   // best of several grid sizes
+        const unsigned grid = (unsigned)cus * per_cu;
+        if (time_ms([&] { hipLaunchKernelGGL(stream_kernel<0>, dim3(grid), dim3(256), 0, 0, a, b, n4, sink); }, 5, &ms)) return 1;
+        if (bytes / (ms * 1e-3) / 1e9 > gbs[0]) gbs[0] = bytes / (ms * 1e-3) / 1e9;
+        if (time_ms([&] { hipLaunchKernelGGL(stream_kernel<1>, dim3(grid), dim3(256), 0, 0, a, b, n4, sink); }, 5, &ms)) return 1;
+        if (2.0 * bytes / (ms * 1e-3) / 1e9 > gbs[1]) gbs[1] = 2.0 * bytes / (ms * 1e-3) / 1e9;
+        if (time_ms([&] { hipLaunchKernelGGL(stream_kernel<2>, dim3(grid), dim3(256), 0, 0, a, a, n4, sink); }, 5, &ms)) return 1;
+        if (2.0 * bytes / (ms * 1e-3) / 1e9 > gbs[2]) gbs[2] = 2.0 * bytes / (ms * 1e-3) / 1e9;
+    }
+    CK(hipFree(a));
+    CK(hipFree(b));
+    CK(hipFree(sink));
+    printf("{\"device\": \"%s\", \"compute_units\": %d, \"clock_mhz\": %d, "
+           "\"mfma_bf16_tflops\": {\"one_wave_per_simd\": %.1f, \"two_waves_per_simd\": %.1f}, "
+           "\"mfma_f32_tflops\": {\"one_wave_per_simd\": %.1f, \"two_waves_per_simd\": %.1f}, "
+           "\"hbm_gbs\": {\"read\": %.0f, \"copy_read_plus_write\": %.0f, \"read_modify_write\": %.0f}, "
+           "\"buffer_gib\": 4}\n",
+           prop.gcnArchName, cus, prop.clockRate / 1000, tf[0], tf[1], tf[2], tf[3], gbs[0], gbs[1], gbs[2]);
+    return 0;
+}
