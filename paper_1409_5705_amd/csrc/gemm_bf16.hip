@@ -28,11 +28,13 @@
 //     load writes 64 lanes x 16 bytes = 8 consecutive LDS rows; the swizzle is
 //     applied on the global side (each lane fetches the chunk that belongs in
 //     its slot).
-//   * Two LDS stages of 64 KiB.  The loads of slice s+2 are issued as soon as
-//     every wavefront has read the last fragments of slice s, spread over the
-//     last two k-steps of the slice (one load per two MFMAs: a burst of loads
-//     blocks the wavefront in the memory-issue stage while the MFMA pipe runs
-//     dry), and have one whole slice of MFMA work (~1 us) to land.  Fragments
+//   * Two LDS stages of 64 KiB.  The loads of slice s+2 may start as soon as
+//     every wavefront has read the last fragments of slice s (middle of its
+//     third k-step) and must have landed when slice s+1 ends; they are spread
+//     over the two and a half k-steps in between, about one per three MFMAs
+//     (a burst of loads blocks the wavefront in the memory-issue stage while the
+//     MFMA pipe runs dry), and the last of them still has one and a half
+//     k-steps to land.  Fragments
 //     are double-buffered in registers across the barriers, so the MFMA pipe
 //     does not drain at a slice boundary.  Two workgroup barriers per k-slice.
 //   * The loader permutes the rows of the B tile inside LDS so that the four
@@ -69,6 +71,19 @@ constexpr int LDS_BYTES = 2 * STAGE;
 // line is touched once per launch; left at the default policy they sweep the
 // operand panels, which ARE reused, out of the 4 MiB L2 of the XCD).
 constexpr int C_POLICY = 2;
+// Load schedule: of the 16 direct loads a wavefront issues per k-slice, N2B go out
+// in the second half of k-step 2 of the slice two before the one they fetch (as
+// soon as its LDS stage is free), N3 in k-step 3, N0 in k-step 0 of the next
+// slice and N1 in its k-step 1, evenly spaced between the MFMAs.  Measured at the
+// headline shape: 8,8,0,0 (everything at once) 5.42 ms forward, 4,6,6,0 5.22,
+// 6,5,5,0 / 5,6,5,0 / 4,7,5,0 the same, 2,6,6,2 5.34, 4,4,4,4 5.43 (the last
+// loads then land too late for the next barrier).
+#ifndef SFB_SCHED
+#define SFB_SCHED 4, 6, 6, 0
+#endif
+constexpr int SCHED[4] = {SFB_SCHED};
+constexpr int N2B = SCHED[0], N3 = SCHED[1], N0 = SCHED[2], N1 = SCHED[3];
+static_assert(N2B + N3 + N0 + N1 == 16 && N2B >= 0 && N3 >= 0 && N0 >= 0 && N1 >= 0, "16 loads per slice");
 constexpr int EPD = 4;                   // epilogue: blocks of C loads in flight + the one being stored
 
 enum Mode : int { MODE_FWD = 0, MODE_APPLY = 1 };
@@ -362,50 +377,71 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     issue();
     wait_all_vmem();
     __syncthreads();
-    issue();
+    // (the first k-steps of the loop issue the rest of slice 1)
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (j < N2B + N3) issue_one(j);
     read_frags(f0, 0);
     // One k-slice (slice s, living in stage s & 1; f0 holds its first fragments).
-    // The 16 direct loads of slice s+2 are spread over the last two k-steps, one
-    // load per two MFMAs: a burst of loads blocks the wavefront in the
-    // memory-issue stage while the MFMA pipe runs dry.  They are unconditional
-    // (past the last slice they re-fetch the last tile into a stage nobody reads).
-    // Two barriers: A, after every wavefront has read the last fragments of
-    // slice s (stage s & 1 may be overwritten); B, after the loads of slice s+1
-    // have landed (they were issued one slice earlier; the 8 loads issued since
-    // A may still be in flight: vmcnt counts in order).
+    // The direct loads are unconditional (past the last slice they re-fetch the
+    // last tile into a stage nobody reads).  Two barriers: A, after every
+    // wavefront has read the last fragments of slice s (stage s & 1 may be
+    // overwritten: the loads of slice s+2 start); B, after the loads of slice s+1
+    // have landed (vmcnt counts in order, so only the N2B loads issued since A may
+    // still be in flight).
     auto mfma_one = [&](const Frags& f, int j) {
         acc[j / TN][j % TN] =
             __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[j / TN], f.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
     };
+    // i-th of n loads goes after MFMA (2 i + 1) m / (2 n) of the m MFMAs of the step; -1: no load after MFMA j
+    auto slot = [](int j, int n, int m) {
+        for (int i = 0; i < n; ++i)
+            if (j == (2 * i + 1) * m / (2 * n)) return i;
+        return -1;
+    };
     auto slice_body = [&](auto first_tag) {
         read_frags(f1, 1);
-        if constexpr (decltype(first_tag)::value)
-            mfma_step_first(f0);
-        else
-            mfma_step(f0);
+        {   // k-step 0
+            const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                if constexpr (decltype(first_tag)::value)
+                    acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.a[j / TN], f0.b[j % TN], zero, 0, 0, 0);
+                else
+                    mfma_one(f0, j);
+                if (slot(j, N0, 16) >= 0) issue_one(N2B + N3 + slot(j, N0, 16));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (N1 == 0) issue_done();
+        }
         read_frags(f0, 2);
-        mfma_step(f1);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {                     // k-step 1
+            mfma_one(f1, j);
+            if (slot(j, N1, 16) >= 0) issue_one(N2B + N3 + N0 + slot(j, N1, 16));
+            if (N1 > 0) __builtin_amdgcn_sched_barrier(0);
+        }
+        if (N1 > 0) issue_done();
         read_frags(f1, 3);
 #pragma unroll
         for (int j = 0; j < 8; ++j) mfma_one(f0, j);
         __syncthreads();                                   // A
 #pragma unroll
-        for (int j = 8; j < 16; ++j) {
+        for (int j = 8; j < 16; ++j) {                     // first loads of slice s+2
             mfma_one(f0, j);
-            issue_one(j - 8);
+            if (slot(j - 8, N2B, 8) >= 0) issue_one(slot(j - 8, N2B, 8));
             __builtin_amdgcn_sched_barrier(0);
         }
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N2B) : "memory");   // everything but those: slice s+1 is in LDS
         __syncthreads();                                   // B
         flip_stage();
         read_frags(f0, 0);   // (after the last slice: a stage nobody uses)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
+        for (int j = 0; j < 16; ++j) {                     // k-step 3
             mfma_one(f1, j);
-            if (j & 1) issue_one(8 + j / 2);
+            if (slot(j, N3, 16) >= 0) issue_one(N2B + slot(j, N3, 16));
             __builtin_amdgcn_sched_barrier(0);
         }
-        issue_done();
     };
     for (int64_t t = 0; t < n_my; ++t) {
         int64_t m0, n0;
