@@ -399,9 +399,22 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             if (j == (2 * i + 1) * m / (2 * n)) return i;
         return -1;
     };
+    // One fragment read (i < TM: row block i of A, else row block i - TM of B) of k-step ks.
+    auto read_one = [&](Frags& f, int ks, int i) {
+        if (i < TM)
+            f.a[i] = *reinterpret_cast<const bf16x8*>(lds_bytes + (((i & 1) ? ra1 : ra0) ^ (32u * ks)) + i * 32 * 128);
+        else
+            f.b[i - TM] = *reinterpret_cast<const bf16x8*>(lds_bytes + ((((i - TM) & 1) ? rb1 : rb0) ^ (32u * ks)) +
+                                                           (i - TM) * 32 * 128);
+    };
+    // The instruction order of a slice is fixed by hand (a scheduling barrier after
+    // every MFMA): left to itself the compiler sinks the fragment reads of the next
+    // k-step to just before their first use, and the wavefront then waits out the
+    // LDS latency with an idle MFMA pipe several times per slice.  The eight reads
+    // of the next k-step follow the first MFMAs of the current one, one each (two
+    // each in k-step 2, whose reads must be over before barrier A).
     auto slice_body = [&](auto first_tag) {
-        read_frags(f1, 1);
-        {   // k-step 0
+        {   // k-step 0: MFMAs on f0, reads of k-step 1 into f1, N0 loads
             const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
@@ -409,22 +422,29 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                     acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.a[j / TN], f0.b[j % TN], zero, 0, 0, 0);
                 else
                     mfma_one(f0, j);
+                if (j < 8) read_one(f1, 1, j);
                 if (slot(j, N0, 16) >= 0) issue_one(N2B + N3 + slot(j, N0, 16));
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (N1 == 0) issue_done();
         }
-        read_frags(f0, 2);
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {                     // k-step 1
+        for (int j = 0; j < 16; ++j) {                     // k-step 1: MFMAs on f1, reads of k-step 2 into f0
             mfma_one(f1, j);
+            if (j < 8) read_one(f0, 2, j);
             if (slot(j, N1, 16) >= 0) issue_one(N2B + N3 + N0 + slot(j, N1, 16));
-            if (N1 > 0) __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (N1 > 0) issue_done();
-        read_frags(f1, 3);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) mfma_one(f0, j);
+        for (int j = 0; j < 8; ++j) {                      // k-step 2: MFMAs on f0, reads of k-step 3 into f1
+            mfma_one(f0, j);
+            if (j < 4) {
+                read_one(f1, 3, 2 * j);
+                read_one(f1, 3, 2 * j + 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
         __syncthreads();                                   // A
 #pragma unroll
         for (int j = 8; j < 16; ++j) {                     // first loads of slice s+2
@@ -435,10 +455,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N2B) : "memory");   // everything but those: slice s+1 is in LDS
         __syncthreads();                                   // B
         flip_stage();
-        read_frags(f0, 0);   // (after the last slice: a stage nobody uses)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {                     // k-step 3
-            mfma_one(f1, j);
+        for (int j = 0; j < 16; ++j) {                     // k-step 3: MFMAs on f1, reads of the next slice's k-step 0
+            mfma_one(f1, j);                               // (after the last slice: of a stage nobody uses)
+            if (j < 8) read_one(f0, 0, j);
             if (slot(j, N3, 16) >= 0) issue_one(N2B + slot(j, N3, 16));
             __builtin_amdgcn_sched_barrier(0);
         }
