@@ -255,6 +255,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB elementwise copy kernel (reference for HBM byte counters)")
+    ap.add_argument("--layout", choices=["split", "fp32"], default="split",
+                    help="mlr_large_bf16: how the library keeps W between steps: 'split' = the two 16-bit planes of "
+                         "sfb_split_attach (same bits, no separate working copy), 'fp32' = the fp32 array plus a bf16 "
+                         "working copy (sfb_shadow_attach)")
     ap.add_argument("--no-shadow", action="store_true",
                     help="do not attach a bf16 working copy of W (the forward then converts W on every call)")
     ap.add_argument("--graph", action="store_true",
@@ -323,7 +327,10 @@ def main():
         ys.append(torch.from_numpy(y).to(dev))
     U = torch.empty((B, J), dtype=torch.bfloat16, device=dev)
     ctx = sfb.Context(0)
-    if not args.no_shadow:
+    split = args.layout == "split" and not args.no_shadow
+    if split:
+        ctx.sfb_split_attach(W)      # W as two 16-bit planes (setup, like W itself): the planes are the parameters
+    elif not args.no_shadow:
         ctx.sfb_shadow_attach(W)     # bf16 working copy of W, kept current by sfb_apply (setup, like W itself)
 
     def step(i):
@@ -357,6 +364,9 @@ def main():
     prof = ctx.sfb_profile_collect()
     ctx.sfb_profile_enable(False)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    if split:
+        ctx.sfb_split_export(W)      # (outside the timed region: the fp32 array is only a snapshot in this layout)
+        torch.cuda.synchronize()
     assert bool(torch.isfinite(W[:1024]).all())
 
     # per-kernel averages from the HIP events recorded on the library's stream
@@ -370,9 +380,9 @@ def main():
     gemm_flops = 2.0 * B * J * D                             # per GEMM stage
     # algorithmic HBM bytes per launch (the bf16 working copy of W counts: read by forward, written by apply)
     wb = 2 if not args.no_shadow else 4
-    fwd_bytes = J * D * wb + B * D * 2 + B * J * 4           # W (copy) read once, X, logits written
-    app_bytes = 2 * J * D * 4 + (J * D * 2 if not args.no_shadow else 0) + B * J * 2 + B * D * 2
-    # ^ W read + written once, bf16 copy written, U^T, V^T read
+    fwd_bytes = J * D * wb + B * D * 2 + B * J * 4           # W (copy / high plane) read once, X, logits written
+    app_bytes = 2 * J * D * 4 + (J * D * 2 if (not args.no_shadow and not split) else 0) + B * J * 2 + B * D * 2
+    # ^ W read + written once (4 bytes per element each way in either layout), bf16 copy written (fp32 layout), U^T, V^T read
     tr_bytes = 2 * (B * J * 2 + B * D * 2)                   # U, V read; U^T, V^T written
     smx_bytes = B * J * 4 + B * J * 2                        # logits read once, U written
     stages = {
@@ -400,9 +410,9 @@ def main():
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": stages["forward_gemm"]["mfma_frac"],
                 "traffic": traffic.get("sf_gemm_kernel<0>")}
     else:
-        roof = {"kernel": "sf_gemm_kernel<1> (apply)", "bound": "hbm", "achieved": stages["apply_gemm"]["hbm_gbs"],
+        roof = {"kernel": ("sf_gemm_kernel<2> (apply on the two planes)" if split else "sf_gemm_kernel<1> (apply)"), "bound": "hbm", "achieved": stages["apply_gemm"]["hbm_gbs"],
                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": stages["apply_gemm"]["hbm_frac"],
-                "traffic": traffic.get("sf_gemm_kernel<1>")}
+                "traffic": traffic.get("sf_gemm_kernel<2>" if split else "sf_gemm_kernel<1>")}
     roof["traffic_unit"] = "bytes per launch (rocprofv3 --pmc, separate run; see profiles/)"
 
     out = {
@@ -419,7 +429,9 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "mlr_large_bf16: MLR J=325000 D=10000 B=N=1024, bf16 X/U/V, fp32 W and accumulate, "
-                               "X ~ N(0,1) with 90% zeros stored " + ("as CSR rows" if args.csr else "dense") + ", eta=0.001",
+                               "X ~ N(0,1) with 90% zeros stored " + ("as CSR rows" if args.csr else "dense") + ", eta=0.001; W kept as "
+                               + ("two 16-bit planes (hi = bf16 operand of the forward, lo = the other half of the fp32 word)"
+                                  if split else "an fp32 array plus a bf16 working copy"),
                    "J": J, "D": D, "B": B, "rank1_terms_per_step": B},
         "tflops_gemm_stages": 2 * gemm_flops / (ms_per_step * 1e-3) / 1e12,
         "mfma_frac_gemm_stages": 2 * gemm_flops / ((fwd_ms + app_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,

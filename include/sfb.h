@@ -98,6 +98,32 @@ int64_t sfb_shadow_bytes(int64_t J, int64_t D);
 int sfb_shadow_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* dev_ptr, int64_t bytes);
 int sfb_shadow_detach(sfb_ctx* ctx);
 
+/*
+ * Optional split storage of one parameter matrix, for the bf16 multiclass-logistic
+ * path (instead of a working copy, not in addition to one).  The fp32 word of every
+ * element is kept as two 16-bit halves in two separate planes with 128-byte-aligned
+ * rows: hi = (bits + 0x8000) >> 16, which is the value rounded to bf16 (to nearest,
+ * ties away from zero), and lo = bits & 0xffff; bits = (hi << 16) + sign_extend(lo)
+ * modulo 2^32, exactly.  The forward contraction reads the hi plane as its bf16
+ * operand; sfb_apply reads and writes both planes, i.e. the same 8 bytes per
+ * element as a read-modify-write of the fp32 array, with the same fp32 arithmetic
+ * and the same resulting bits, but without the third write that keeps a separate
+ * working copy current.
+ * sfb_split_attach converts W into the caller-allocated buffer (sfb_split_bytes,
+ * 256-byte aligned; never freed by the library) and remembers (W, J, D).  While
+ * attached, the planes ARE the parameters and the fp32 array W is a stale
+ * snapshot: sfb_compute_sf(SFB_MLR, bf16), sfb_mlr_sf_csr(bf16) and sfb_apply /
+ * sfb_apply_signed / sfb_apply_csr with bf16 factors on that W work on the planes
+ * (W itself is neither read nor written); every other call that would read or write
+ * the fp32 array of that W returns SFB_EINVAL.  sfb_split_export writes the current
+ * parameters back into W (the matrix stays attached); sfb_split_detach forgets the
+ * planes without exporting.  A second sfb_split_attach of the same W re-converts it.
+ */
+int64_t sfb_split_bytes(int64_t J, int64_t D);
+int sfb_split_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* dev_ptr, int64_t bytes);
+int sfb_split_export(sfb_ctx* ctx, float* W);
+int sfb_split_detach(sfb_ctx* ctx);
+
 /* Hands the context a caller-allocated device buffer (256-byte aligned) to use
  * as scratch until replaced.  The library never frees it.  Its contents are
  * undefined after any call. */

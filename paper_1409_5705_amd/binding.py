@@ -85,6 +85,14 @@ def lib():
         L.sfb_shadow_attach.restype = ctypes.c_int
         L.sfb_shadow_detach.argtypes = [vp]
         L.sfb_shadow_detach.restype = ctypes.c_int
+        L.sfb_split_bytes.argtypes = [i64, i64]
+        L.sfb_split_bytes.restype = i64
+        L.sfb_split_attach.argtypes = [vp, vp, i64, i64, vp, i64]
+        L.sfb_split_attach.restype = ctypes.c_int
+        L.sfb_split_export.argtypes = [vp, vp]
+        L.sfb_split_export.restype = ctypes.c_int
+        L.sfb_split_detach.argtypes = [vp]
+        L.sfb_split_detach.restype = ctypes.c_int
         L.sfb_set_workspace.argtypes = [vp, vp, i64]
         L.sfb_set_workspace.restype = ctypes.c_int
         L.sfb_compute_sf.argtypes = [vp, i32, vp, i64, i64, ctypes.POINTER(sfb_batch), vp, vp, vp]
@@ -214,6 +222,28 @@ class Context:
 
     def sfb_shadow_detach(self):
         self._check(lib().sfb_shadow_detach(self._h), "sfb_shadow_detach")
+        self._shadow = None
+
+    # -- W kept as two 16-bit planes --------------------------------------------
+    def sfb_split_attach(self, W):
+        """Allocates (once) the two planes and converts W into them; from then on W's fp32 array is stale
+        until sfb_split_export.  Call again to re-convert after changing W yourself."""
+        J, D = W.shape
+        need = lib().sfb_split_bytes(J, D)
+        if need < 0:
+            raise SfbError(int(need), "sfb_split_bytes")
+        buf = self._shadow[1] if self._shadow is not None and self._shadow[1].numel() >= need else \
+            torch.empty(need, dtype=torch.uint8, device=self.device)
+        self._check(lib().sfb_split_attach(self._h, _ptr(W, "W", dtype=torch.float32), J, D, buf.data_ptr(),
+                                           buf.numel()), "sfb_split_attach")
+        self._shadow = (W, buf)
+
+    def sfb_split_export(self, W):
+        """Enqueues the write-back of the current parameters into W's fp32 array."""
+        self._check(lib().sfb_split_export(self._h, _ptr(W, "W", dtype=torch.float32)), "sfb_split_export")
+
+    def sfb_split_detach(self):
+        self._check(lib().sfb_split_detach(self._h), "sfb_split_detach")
         self._shadow = None
 
     def close(self):

@@ -84,15 +84,18 @@ constexpr int C_POLICY = 2;
 constexpr int SCHED[4] = {SFB_SCHED};
 constexpr int N2B = SCHED[0], N3 = SCHED[1], N0 = SCHED[2], N1 = SCHED[3];
 static_assert(N2B + N3 + N0 + N1 == 16 && N2B >= 0 && N3 >= 0 && N0 >= 0 && N1 >= 0, "16 loads per slice");
-constexpr int EPD = 4;                   // epilogue: blocks of C loads in flight + the one being stored
+constexpr int EPD = 4;                   // epilogue: blocks of C loads in flight + the one being stored (2: +1.5 %, 3 and 5: the same)
 
-enum Mode : int { MODE_FWD = 0, MODE_APPLY = 1 };
+// MODE_SPLIT: the apply on a matrix stored as two 16-bit planes (see split_from_w_kernel):
+// `shadow` is the high plane, `lo` the low one, C is not touched.
+enum Mode : int { MODE_FWD = 0, MODE_APPLY = 1, MODE_SPLIT = 2 };
 
 struct Params {
     const uint16_t* A;  // bf16 [M][lda], lda % 64 == 0, k zero-padded to K
     const uint16_t* B;  // bf16 [N][ldb]
     float* C;           // [M][ldc]
-    uint16_t* shadow;   // apply: bf16 copy of C to refresh ([M][ld_shadow]), or null
+    uint16_t* shadow;   // apply: bf16 copy of C to refresh ([M][ld_shadow]), or null; split: high plane
+    uint16_t* lo;       // split: low plane ([M][ld_shadow])
     int64_t M, N, K;    // K % 64 == 0
     int64_t lda, ldb, ldc, ld_shadow;
     float eta;
@@ -108,6 +111,16 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     bf16x2 h = __builtin_convertvector(f, bf16x2);  // round to nearest even
     return __builtin_bit_cast(uint32_t, h);
 }
+
+// A parameter matrix kept as two 16-bit planes: hi = (bits + 0x8000) >> 16 is the
+// value rounded to bf16 (to nearest, ties away from zero), lo = bits & 0xffff; the
+// fp32 bit pattern is (hi << 16) + sign_extend(lo) modulo 2^32, exactly.
+__device__ __forceinline__ float split_join(uint32_t hi16, uint32_t lo16)
+{
+    return __uint_as_float((hi16 << 16) + (uint32_t)(int32_t)(int16_t)(uint16_t)lo16);
+}
+__device__ __forceinline__ uint32_t split_hi(float v) { return (__float_as_uint(v) + 0x8000u) >> 16; }
+__device__ __forceinline__ uint32_t split_lo(float v) { return __float_as_uint(v) & 0xffffu; }
 
 // Chunk-slot swizzle of tile row r: chunk c of the row sits in slot c ^ swz(r).
 // Chosen by measurement: an MFMA operand read (32 consecutive rows at chunk g,
@@ -307,9 +320,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     };
     auto epilogue_tile = [&](int64_t m0, int64_t n0, auto guard_tag) {
         constexpr bool GUARD = decltype(guard_tag)::value;
-        const auto crs = make_rsrc(p.C + (m0 + wm0) * p.ldc + n0 + wn0);
+        const auto crs = make_rsrc(MODE == MODE_SPLIT ? p.C : p.C + (m0 + wm0) * p.ldc + n0 + wn0);
         const bool has_shadow = p.shadow && !(p.dbg & 8);
         const auto srs = make_rsrc(has_shadow ? p.shadow + (m0 + wm0) * p.ld_shadow + n0 + wn0 : p.shadow);
+        const auto lrs = make_rsrc(MODE == MODE_SPLIT ? p.lo + (m0 + wm0) * p.ld_shadow + n0 + wn0 : p.lo);
         const int rows_left = (int)(p.M - (m0 + wm0) < 4 * BM ? p.M - (m0 + wm0) : 4 * BM) - 4 * g;   // for this lane
         const uint32_t row_c = (uint32_t)p.ldc * 4u, row_s = (uint32_t)p.ld_shadow * 2u;
         const uint32_t lane_c = (uint32_t)(4 * g) * row_c + (uint32_t)l32 * 16u;
@@ -326,18 +340,26 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             for (int e = 0; e < 8; ++e) {
                 const int i = (q & 1) * 8 + e, dr = (q >> 1) * 32 + 8 * (i / 4) + (i % 4);
                 dst[e] = u32x4{0u, 0u, 0u, 0u};
-                if (col_ok && (!GUARD || dr < rows_left))
-                    dst[e] = __builtin_amdgcn_raw_buffer_load_b128(crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
+                if (col_ok && (!GUARD || dr < rows_left)) {
+                    if (MODE == MODE_SPLIT) {   // four columns of the high plane, then of the low plane
+                        const u32x2 h = __builtin_amdgcn_raw_buffer_load_b64(srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
+                        const u32x2 l = __builtin_amdgcn_raw_buffer_load_b64(lrs, lane_s, (uint32_t)dr * row_s, C_POLICY);
+                        const uint32_t h0 = h[0], h1 = h[1], l0 = l[0], l1 = l[1];
+                        dst[e] = u32x4{h0, h1, l0, l1};
+                    } else {
+                        dst[e] = __builtin_amdgcn_raw_buffer_load_b128(crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
+                    }
+                }
             }
         };
-        if (MODE == MODE_APPLY) {
+        if (MODE != MODE_FWD) {
 #pragma unroll
             for (int q = 0; q < EPD - 1 && q < NQ; ++q) load_block(q, w[q % EPD]);
         }
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const int ta = q >> 1;
-            if (MODE == MODE_APPLY && q + EPD - 1 < NQ) load_block(q + EPD - 1, w[(q + EPD - 1) % EPD]);
+            if (MODE != MODE_FWD && q + EPD - 1 < NQ) load_block(q + EPD - 1, w[(q + EPD - 1) % EPD]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int i = (q & 1) * 8 + e, dr = ta * 32 + 8 * (i / 4) + (i % 4);
@@ -348,6 +370,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                         const u32x4 out = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2),
                                            __float_as_uint(v3)};
                         __builtin_amdgcn_raw_buffer_store_b128(out, crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
+                    } else if (MODE == MODE_SPLIT) {
+                        const uint32_t hA = w[q % EPD][e][0], hB = w[q % EPD][e][1], lA = w[q % EPD][e][2],
+                                       lB = w[q % EPD][e][3];
+                        const float n0f = split_join(hA & 0xffffu, lA & 0xffffu) - p.eta * v0;
+                        const float n1f = split_join(hA >> 16, lA >> 16) - p.eta * v1;
+                        const float n2f = split_join(hB & 0xffffu, lB & 0xffffu) - p.eta * v2;
+                        const float n3f = split_join(hB >> 16, lB >> 16) - p.eta * v3;
+                        const u32x2 oh = {split_hi(n0f) | (split_hi(n1f) << 16), split_hi(n2f) | (split_hi(n3f) << 16)};
+                        const u32x2 ol = {split_lo(n0f) | (split_lo(n1f) << 16), split_lo(n2f) | (split_lo(n3f) << 16)};
+                        __builtin_amdgcn_raw_buffer_store_b64(oh, srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
+                        __builtin_amdgcn_raw_buffer_store_b64(ol, lrs, lane_s, (uint32_t)dr * row_s, C_POLICY);
                     } else {
                         const uint32_t o0 = w[q % EPD][e][0], o1 = w[q % EPD][e][1], o2 = w[q % EPD][e][2],
                                        o3 = w[q % EPD][e][3];
@@ -549,6 +582,48 @@ __global__ __launch_bounds__(256) void pad_rows_bf16_kernel(const SrcT* __restri
     }
 }
 
+// W[J][D] fp32 -> the two planes ([J][pitch], columns D.. zero), 8 elements a thread; and back.
+__global__ __launch_bounds__(256) void split_from_w_kernel(const float* __restrict__ W, uint16_t* __restrict__ hi,
+                                                           uint16_t* __restrict__ lo, int64_t rows, int64_t cols,
+                                                           int64_t pitch)
+{
+    const int64_t chunks = pitch / 8, total = rows * chunks;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+        const int64_t r = idx / chunks, c = (idx % chunks) * 8;
+        u32x4 h = {0u, 0u, 0u, 0u}, l = {0u, 0u, 0u, 0u};
+        if (c < cols) {   // cols % 8 == 0
+            const floatx4 a = *reinterpret_cast<const floatx4*>(W + r * cols + c);
+            const floatx4 b = *reinterpret_cast<const floatx4*>(W + r * cols + c + 4);
+            const float a0 = a[0], a1 = a[1], a2 = a[2], a3 = a[3], b0 = b[0], b1 = b[1], b2 = b[2], b3 = b[3];
+            h = u32x4{split_hi(a0) | (split_hi(a1) << 16), split_hi(a2) | (split_hi(a3) << 16),
+                      split_hi(b0) | (split_hi(b1) << 16), split_hi(b2) | (split_hi(b3) << 16)};
+            l = u32x4{split_lo(a0) | (split_lo(a1) << 16), split_lo(a2) | (split_lo(a3) << 16),
+                      split_lo(b0) | (split_lo(b1) << 16), split_lo(b2) | (split_lo(b3) << 16)};
+        }
+        *reinterpret_cast<u32x4*>(hi + r * pitch + c) = h;
+        *reinterpret_cast<u32x4*>(lo + r * pitch + c) = l;
+    }
+}
+
+__global__ __launch_bounds__(256) void w_from_split_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
+                                                           float* __restrict__ W, int64_t rows, int64_t cols,
+                                                           int64_t pitch)
+{
+    const int64_t chunks = cols / 8, total = rows * chunks;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+        const int64_t r = idx / chunks, c = (idx % chunks) * 8;
+        const u32x4 h = *reinterpret_cast<const u32x4*>(hi + r * pitch + c);
+        const u32x4 l = *reinterpret_cast<const u32x4*>(lo + r * pitch + c);
+        const uint32_t h0 = h[0], h1 = h[1], h2 = h[2], h3 = h[3], l0 = l[0], l1 = l[1], l2 = l[2], l3 = l[3];
+        const floatx4 a = {split_join(h0 & 0xffffu, l0 & 0xffffu), split_join(h0 >> 16, l0 >> 16),
+                           split_join(h1 & 0xffffu, l1 & 0xffffu), split_join(h1 >> 16, l1 >> 16)};
+        const floatx4 b = {split_join(h2 & 0xffffu, l2 & 0xffffu), split_join(h2 >> 16, l2 >> 16),
+                           split_join(h3 & 0xffffu, l3 & 0xffffu), split_join(h3 >> 16, l3 >> 16)};
+        *reinterpret_cast<floatx4*>(W + r * cols + c) = a;
+        *reinterpret_cast<floatx4*>(W + r * cols + c + 4) = b;
+    }
+}
+
 int g_forward_dbg = 0;   // timing experiments only: 2 = no epilogue, 8 = no shadow store
 int g_apply_dbg = 0;
 
@@ -562,9 +637,13 @@ hipError_t launch(Params p, hipStream_t stream)
     // 32-bit in-tile byte offsets in the loaders and in the epilogue
     if (p.lda * 2 * BM >= (1LL << 31) || p.ldb * 2 * BN >= (1LL << 31) || p.ldc * 4 * BM >= (1LL << 31))
         return hipErrorInvalidValue;
-    // 16-byte accesses of C, 8-byte accesses of its bf16 copy
-    if (reinterpret_cast<uintptr_t>(p.C) % 16 != 0 || p.ldc % 4 != 0 || p.N % 4 != 0) return hipErrorInvalidValue;
+    // 16-byte accesses of C, 8-byte accesses of its bf16 copy and of the two planes
+    if (p.N % 4 != 0) return hipErrorInvalidValue;
+    if (MODE != MODE_SPLIT && (reinterpret_cast<uintptr_t>(p.C) % 16 != 0 || p.ldc % 4 != 0)) return hipErrorInvalidValue;
     if (p.shadow && (reinterpret_cast<uintptr_t>(p.shadow) % 8 != 0 || p.ld_shadow % 4 != 0))
+        return hipErrorInvalidValue;
+    if (MODE == MODE_SPLIT && (!p.shadow || !p.lo || reinterpret_cast<uintptr_t>(p.lo) % 8 != 0 || p.ld_shadow < p.N ||
+                               p.ld_shadow * 2 * BM >= (1LL << 31)))
         return hipErrorInvalidValue;
     if (p.K <= 0 || p.K % BK != 0 || p.lda % BK != 0 || p.ldb % BK != 0 || p.lda < p.K || p.ldb < p.K)
         return hipErrorInvalidValue;
@@ -650,7 +729,23 @@ hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, con
     return hipGetLastError();
 }
 
-hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, int64_t N, int64_t J, int64_t D, float eta,
+hipError_t launch_split_from_w(const float* W, uint16_t* hi, uint16_t* lo, int64_t J, int64_t D, hipStream_t stream)
+{
+    if (J <= 0 || D <= 0) return hipSuccess;
+    const int64_t pitch = bf16_pitch(D);
+    hipLaunchKernelGGL(split_from_w_kernel, dim3(grid_for(J * (pitch / 8))), dim3(256), 0, stream, W, hi, lo, J, D, pitch);
+    return hipGetLastError();
+}
+
+hipError_t launch_w_from_split(const uint16_t* hi, const uint16_t* lo, float* W, int64_t J, int64_t D, hipStream_t stream)
+{
+    if (J <= 0 || D <= 0) return hipSuccess;
+    hipLaunchKernelGGL(w_from_split_kernel, dim3(grid_for(J * (D / 8))), dim3(256), 0, stream, hi, lo, W, J, D,
+                       bf16_pitch(D));
+    return hipGetLastError();
+}
+
+hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64_t N, int64_t J, int64_t D, float eta,
                              const void* workspace, hipStream_t stream)
 {
     if (N <= 0 || J <= 0 || D <= 0) return hipSuccess;
@@ -666,6 +761,10 @@ hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, int64_t N, int64_t J,
     p.eta = eta;
     p.group_m = 8;               // 8 row-tiles x 4 column tiles under one L2 at a time (measured best of 1..32)
     p.dbg = g_apply_dbg;
+    if (W_lo) {
+        p.lo = W_lo;
+        return launch<MODE_SPLIT>(p, stream);
+    }
     return launch<MODE_APPLY>(p, stream);
 }
 

@@ -64,8 +64,13 @@ int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D);
 uint16_t* apply_bf16_vt(void* workspace, int64_t N, int64_t J);
 hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, const float* coef, int64_t N, int64_t J,
                                        int64_t D, void* workspace, hipStream_t stream);
-hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, int64_t N, int64_t J, int64_t D, float eta,
+// W_lo (nullable): W is kept as two 16-bit planes, W_shadow the high one (the value rounded
+// to bf16) and W_lo the low one; both are updated and the fp32 array W is not touched.
+hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64_t N, int64_t J, int64_t D, float eta,
                              const void* workspace, hipStream_t stream);
+// fp32 W[J][D] <-> planes hi, lo ([J][bf16_pitch(D)] each): bits = (hi << 16) + sign_extend(lo).
+hipError_t launch_split_from_w(const float* W, uint16_t* hi, uint16_t* lo, int64_t J, int64_t D, hipStream_t stream);
+hipError_t launch_w_from_split(const uint16_t* hi, const uint16_t* lo, float* W, int64_t J, int64_t D, hipStream_t stream);
 // Timing experiments (benchmark sweeps): variant / 100 = debug bits; -1 = normal.
 void set_bf16_variant(int forward_variant, int apply_variant);
 

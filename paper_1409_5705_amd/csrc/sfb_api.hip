@@ -58,6 +58,8 @@ struct sfb_ctx {
     const float* shadow_W;
     uint16_t* shadow_buf;
     int64_t shadow_J, shadow_D;
+    // low plane when that matrix is kept as two 16-bit planes (sfb_split_attach); shadow_buf is then the high plane
+    uint16_t* split_lo;
 };
 
 namespace {
@@ -129,6 +131,9 @@ int64_t sc_partial_bytes(int64_t B, int64_t J, int64_t D)
     return round_up(a > b ? a : b);
 }
 
+// True if W is currently kept as two planes by this context: its fp32 array is stale.
+bool is_split(const sfb_ctx* ctx, const float* W) { return ctx->split_lo && ctx->shadow_W == W; }
+
 int check_batch(int32_t model, int64_t J, int64_t D, const sfb_batch* b)
 {
     if (!b || J <= 0 || D <= 0 || b->B < 0) return SFB_EINVAL;
@@ -166,6 +171,7 @@ int sfb_create(sfb_ctx** out, int device_id, void* hip_stream)
     c->shadow_W = nullptr;
     c->shadow_buf = nullptr;
     c->shadow_J = c->shadow_D = 0;
+    c->split_lo = nullptr;
     *out = c;
     return SFB_OK;
 }
@@ -262,6 +268,7 @@ int64_t sfb_shadow_bytes(int64_t J, int64_t D)
 int sfb_shadow_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* dev_ptr, int64_t bytes)
 {
     if (!ctx || !W || !dev_ptr || !aligned16(W)) return SFB_EINVAL;
+    if (ctx->split_lo) return SFB_EINVAL;   // a matrix is attached in split form: detach it first
     const int64_t need = sfb_shadow_bytes(J, D);
     if (need < 0) return SFB_EINVAL;
     if (bytes < need) return SFB_ENOWS;
@@ -277,10 +284,55 @@ int sfb_shadow_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* 
 
 int sfb_shadow_detach(sfb_ctx* ctx)
 {
-    if (!ctx) return SFB_EINVAL;
+    if (!ctx || ctx->split_lo) return SFB_EINVAL;
     ctx->shadow_W = nullptr;
     ctx->shadow_buf = nullptr;
     ctx->shadow_J = ctx->shadow_D = 0;
+    return SFB_OK;
+}
+
+int64_t sfb_split_bytes(int64_t J, int64_t D)
+{
+    const int64_t plane = sfb_shadow_bytes(J, D);
+    return plane < 0 ? plane : 2 * plane;
+}
+
+int sfb_split_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* dev_ptr, int64_t bytes)
+{
+    if (!ctx || !W || !dev_ptr || !aligned16(W)) return SFB_EINVAL;
+    if (ctx->shadow_buf && !(ctx->split_lo && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D))
+        return SFB_EINVAL;   // something else is attached (the same matrix in split form may be refreshed)
+    const int64_t plane = sfb_shadow_bytes(J, D);
+    if (plane < 0) return SFB_EINVAL;
+    if (bytes < 2 * plane) return SFB_ENOWS;
+    if (reinterpret_cast<uintptr_t>(dev_ptr) % ALIGN != 0) return SFB_EINVAL;
+    SFB_TRY(hipSetDevice(ctx->device));
+    uint16_t* hi = static_cast<uint16_t*>(dev_ptr);
+    uint16_t* lo = hi + plane / 2;
+    SFB_RUN(KID_SHADOW, sfb::launch_split_from_w(W, hi, lo, J, D, ctx->stream));
+    ctx->shadow_W = W;
+    ctx->shadow_buf = hi;
+    ctx->shadow_J = J;
+    ctx->shadow_D = D;
+    ctx->split_lo = lo;
+    return SFB_OK;
+}
+
+int sfb_split_export(sfb_ctx* ctx, float* W)
+{
+    if (!ctx || !W || !ctx->split_lo || ctx->shadow_W != W) return SFB_EINVAL;
+    SFB_TRY(hipSetDevice(ctx->device));
+    SFB_RUN(KID_SHADOW, sfb::launch_w_from_split(ctx->shadow_buf, ctx->split_lo, W, ctx->shadow_J, ctx->shadow_D, ctx->stream));
+    return SFB_OK;
+}
+
+int sfb_split_detach(sfb_ctx* ctx)
+{
+    if (!ctx || !ctx->split_lo) return SFB_EINVAL;
+    ctx->shadow_W = nullptr;
+    ctx->shadow_buf = nullptr;
+    ctx->shadow_J = ctx->shadow_D = 0;
+    ctx->split_lo = nullptr;
     return SFB_OK;
 }
 
@@ -310,6 +362,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
     if (rc != SFB_OK) return rc;
     const int64_t B = batch->B;
     if (!W || !aligned16(W)) return SFB_EINVAL;
+    if (is_split(ctx, W) && !(model == SFB_MLR && batch->in_dtype == SFB_BF16)) return SFB_EINVAL;   // fp32 array is stale
     if (B == 0) return SFB_OK;
     if (!batch->X || !U || !aligned16(batch->X) || !aligned16(U) || (V && !aligned16(V))) return SFB_EINVAL;
     const bool has_shadow = ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D;
@@ -420,6 +473,7 @@ static int apply_impl(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* 
                               : sfb_apply_workspace_bytes(J, D, N, sf_dtype);
     if (need < 0) return (int)need;
     if (need > 0 && (!ctx->ws || ctx->ws_bytes < need)) return SFB_ENOWS;
+    if (is_split(ctx, W) && (sf_dtype != SFB_BF16 || ctx->shadow_J != J || ctx->shadow_D != D)) return SFB_EINVAL;
     SFB_TRY(hipSetDevice(ctx->device));
     if (sf_dtype == SFB_F32) {
         const int64_t part = round_up(sfb::gemm_f32_partial_bytes(J, D, N));
@@ -447,7 +501,8 @@ static int apply_impl(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* 
         SFB_RUN(KID_APPLY_TRANSPOSE,
                 sfb::launch_apply_bf16_transpose(static_cast<const uint16_t*>(U), static_cast<const uint16_t*>(V), coef,
                                                  N, J, D, ctx->ws, ctx->stream));
-        SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, Wb, N, J, D, eta, ctx->ws, ctx->stream));
+        SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, Wb, is_split(ctx, W) ? ctx->split_lo : nullptr, N, J, D, eta,
+                                                       ctx->ws, ctx->stream));
     }
     return SFB_OK;
 }
@@ -537,6 +592,7 @@ int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb
     if (B == 0) return SFB_OK;
     if (!y || !U || !aligned16(U)) return SFB_EINVAL;
     const bool has_shadow = ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D;
+    if (is_split(ctx, W) && (!bf16 || !has_shadow)) return SFB_EINVAL;
     int64_t need = sfb_mlr_sf_csr_workspace_bytes(J, D, B, X->dtype);
     if (need < 0) return (int)need;
     if (bf16 && has_shadow) need -= sfb_shadow_bytes(J, D);
@@ -599,6 +655,7 @@ int sfb_apply_csr(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, c
     SFB_TRY(hipSetDevice(ctx->device));
     hipStream_t st = ctx->stream;
     const bool has_shadow = ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D;
+    if (is_split(ctx, W) && (V->dtype != SFB_BF16 || !has_shadow)) return SFB_EINVAL;
     if (V->dtype == SFB_F32) {
         const int64_t part = round_up(sfb::gemm_f32_partial_bytes(J, D, N));
         float* Vd = reinterpret_cast<float*>(ctx->ws + part);
@@ -622,7 +679,8 @@ int sfb_apply_csr(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, c
     SFB_RUN(KID_CSR, sfb::launch_csr_scatter(V->indptr, V->indices, V->values, true, coef, Vt, N, D, V->nnz, 1, Np, st));
     SFB_RUN(KID_APPLY_TRANSPOSE, sfb::launch_apply_bf16_transpose(static_cast<const uint16_t*>(U), nullptr, nullptr, N, J,
                                                                   D, ctx->ws, st));
-    SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, has_shadow ? ctx->shadow_buf : nullptr, N, J, D, eta, ctx->ws, st));
+    SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, has_shadow ? ctx->shadow_buf : nullptr,
+                                                   is_split(ctx, W) ? ctx->split_lo : nullptr, N, J, D, eta, ctx->ws, st));
     return SFB_OK;
 }
 
@@ -637,7 +695,7 @@ int sfb_sdca_mlr_sf(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const fl
 {
     if (!ctx || J <= 0 || D <= 0 || B < 0 || N <= 0) return SFB_EINVAL;
     if (!(lambda > 0.f) || !(beta > 0.f) || !(beta <= 1.f)) return SFB_EINVAL;
-    if (!W || !aligned16(W)) return SFB_EINVAL;
+    if (!W || !aligned16(W) || is_split(ctx, W)) return SFB_EINVAL;
     if (B == 0) return SFB_OK;
     if (!X || !P || !dU || !aligned16(X) || !aligned16(P) || !aligned16(dU)) return SFB_EINVAL;
     const int64_t need = sfb_sdca_workspace_bytes(J, D, B);
@@ -658,7 +716,7 @@ int sfb_sdca_mlr_sf(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const fl
 
 int sfb_dual_to_primal_l2(sfb_ctx* ctx, const float* Z, float* W, int64_t J, int64_t D, float lambda)
 {
-    if (!ctx || !Z || !W || J <= 0 || D <= 0 || !(lambda > 0.f)) return SFB_EINVAL;
+    if (!ctx || !Z || !W || J <= 0 || D <= 0 || !(lambda > 0.f) || is_split(ctx, W) || is_split(ctx, Z)) return SFB_EINVAL;
     SFB_TRY(hipSetDevice(ctx->device));
     SFB_RUN(KID_DUAL_TO_PRIMAL, sfb::launch_div_scalar(Z, W, lambda, J * D, ctx->stream));
     if (ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D)
@@ -668,7 +726,7 @@ int sfb_dual_to_primal_l2(sfb_ctx* ctx, const float* Z, float* W, int64_t J, int
 
 int sfb_prox_rows(sfb_ctx* ctx, float* W, int64_t J, int64_t D, int32_t mode)
 {
-    if (!ctx || !W || J <= 0 || D <= 0) return SFB_EINVAL;
+    if (!ctx || !W || J <= 0 || D <= 0 || is_split(ctx, W)) return SFB_EINVAL;
     if (mode != SFB_PROX_PROJECT && mode != SFB_PROX_NORMALIZE) return SFB_EINVAL;
     SFB_TRY(hipSetDevice(ctx->device));
     SFB_RUN(KID_PROX, sfb::launch_prox_rows(W, J, D, mode, ctx->stream));
