@@ -1,6 +1,6 @@
 """GPU parity at the full size of the headline workload (MLR, J=325,000 classes,
 D=10,000 features, B=1024, bf16 inputs, fp32 W), in the launch configuration the
-bench times.  The oracle cannot finish the whole step in seconds, so:
+bench times (W kept as two 16-bit planes, sfb_split_attach).  The oracle cannot finish the whole step in seconds, so:
 
  * SFs: all J entries of u for a few sampled samples, computed one by one by the
    oracle from the same W and X;
@@ -40,7 +40,7 @@ def big(sfb):
     Xd = torch.from_numpy(S.bf16_bits(X)).to("cuda:0").view(torch.bfloat16)
     yd = torch.from_numpy(y).to("cuda:0")
     ctx = sfb.Context(0)
-    ctx.sfb_shadow_attach(W)      # the configuration the bench times
+    ctx.sfb_split_attach(W)       # the configuration the bench times: W as two 16-bit planes
     yield dict(W=W, X=X, y=y, Xd=Xd, yd=yd, ctx=ctx, J=J, D=D, B=B)
     ctx.close()
 
@@ -79,9 +79,18 @@ def test_large_apply_reconstruction(big, sfb, oracle):
     Uh = S.round_to_bf16(Uh)
     Ud = torch.from_numpy(S.bf16_bits(Uh)).to("cuda:0").view(torch.bfloat16)
     Wz = torch.zeros((J, D), dtype=torch.float32, device="cuda:0")
-    print("large: apply", flush=True)
-    big["ctx"].sfb_apply(Wz, Ud, big["Xd"], 1.0)
+    print("large: apply (on the two planes, as the bench does; then export)", flush=True)
+    c2 = sfb.Context(0)
+    c2.sfb_split_attach(Wz)
+    c2.sfb_apply(Wz, Ud, big["Xd"], 1.0)
+    c2.sfb_split_export(Wz)
     torch.cuda.synchronize()
+    print("large: apply on an fp32 array", flush=True)
+    Wf = torch.zeros((J, D), dtype=torch.float32, device="cuda:0")
+    big["ctx"].sfb_apply(Wf, Ud, big["Xd"], 1.0)
+    torch.cuda.synchronize()
+    assert torch.equal(Wz, Wf)                       # same bits in either storage
+    del Wf
     rows = np.sort(g.choice(J, size=1536, replace=False))
     rows[:4] = [0, 1, 2, 3]; rows[-4:] = [J - 4, J - 3, J - 2, J - 1]
     rows = np.unique(rows)
@@ -99,9 +108,11 @@ def test_large_apply_reconstruction(big, sfb, oracle):
     print("large: column-sum err", e2, flush=True)
     assert e2 < 1e-3
     # second application with the opposite sign restores zero (up to rounding of the sums)
-    big["ctx"].sfb_apply(Wz, Ud, big["Xd"], -1.0)
+    c2.sfb_apply(Wz, Ud, big["Xd"], -1.0)
+    c2.sfb_split_export(Wz)
     torch.cuda.synchronize()
     assert float(Wz.abs().max()) == 0.0
+    c2.close()
 
 
 @pytest.mark.timeout(600)
