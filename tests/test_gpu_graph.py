@@ -94,3 +94,44 @@ def test_mlr_bf16_step_replays_from_a_graph(sfb):
         torch.cuda.synchronize()
         assert torch.equal(W, ref[k]), "replay %d differs from the eager step" % k
     ctx.close()
+
+
+def test_mlr_bf16_step_on_split_storage_replays_from_a_graph(sfb):
+    """The same step with W kept as two 16-bit planes; the export is part of the captured graph."""
+    J, D, B = 1000, 520, 130
+    W0 = dev(S.normal_matrix(J, D, 0.02, seed=3))
+    Xh, yh = S.mlr_batch(J, D, B, seed=3, zero_frac=0.9, bf16=True)
+    X = dev(S.bf16_bits(Xh)).view(torch.bfloat16)
+    y = dev(yh)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx = sfb.Context(0)
+        W = W0.clone()
+        ctx.sfb_split_attach(W)
+        U = torch.empty((B, J), dtype=torch.bfloat16, device="cuda:0")
+
+        def step():
+            ctx.sfb_compute_sf(sfb.SFB_MLR, W, X, Y=y, U=U)
+            ctx.sfb_apply(W, U, X, 0.05)
+            ctx.sfb_split_export(W)
+
+        step()
+        side.synchronize()
+        ref = [W.clone()]
+        for _ in range(2):
+            step()
+            side.synchronize()
+            ref.append(W.clone())
+        W.copy_(W0)
+        ctx.sfb_split_attach(W)                     # planes back to the start
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for k in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(W, ref[k]), "replay %d differs from the eager step" % k
+        junk = torch.randn(1 << 20, device="cuda:0").sum().item()
+        assert np.isfinite(junk)
+    ctx.close()
