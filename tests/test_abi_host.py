@@ -73,6 +73,27 @@ def test_workspace_bytes_logic(sfb):
     assert L.sfb_workspace_bytes(sfb.SFB_MLR, 10, 10, None) == sfb.SFB_EINVAL
 
 
+def test_sizes_of_the_later_entry_points(sfb):
+    L = sfb.lib()
+    # two planes of the size of one bf16 working copy
+    assert L.sfb_split_bytes(104, 72) == 2 * L.sfb_shadow_bytes(104, 72) and L.sfb_split_bytes(104, 70) == sfb.SFB_EINVAL
+    # CSR: bf16 needs no more than the dense call, fp32 a dense copy of X (or V) more
+    b16 = _batch(sfb, B=8, in_dtype=1, sf_dtype=1)
+    assert L.sfb_mlr_sf_csr_workspace_bytes(104, 72, 8, 1) == L.sfb_workspace_bytes(sfb.SFB_MLR, 104, 72, ctypes.byref(b16))
+    b32 = _batch(sfb, B=8)
+    assert L.sfb_mlr_sf_csr_workspace_bytes(104, 72, 8, 0) >= L.sfb_workspace_bytes(sfb.SFB_MLR, 104, 72, ctypes.byref(b32)) + 8 * 72 * 4
+    assert L.sfb_apply_csr_workspace_bytes(104, 72, 10, 1) == L.sfb_apply_workspace_bytes(104, 72, 10, 1)
+    assert L.sfb_apply_csr_workspace_bytes(104, 72, 10, 0) >= 10 * 72 * 4
+    assert L.sfb_apply_signed_workspace_bytes(104, 72, 10, 0) >= 10 * 72 * 4
+    assert L.sfb_mlr_sf_csr_workspace_bytes(104, 72, 8, 5) == sfb.SFB_EINVAL
+    # SDCA: logits of the batch
+    assert L.sfb_sdca_workspace_bytes(100, 64, 8) >= 8 * 100 * 4 and L.sfb_sdca_workspace_bytes(0, 64, 8) == sfb.SFB_EINVAL
+    # calls on a null context
+    assert L.sfb_split_detach(None) == sfb.SFB_EINVAL and L.sfb_split_export(None, None) == sfb.SFB_EINVAL
+    assert L.sfb_csr_check(None, None, None) == sfb.SFB_EINVAL
+    assert L.sfb_sdca_mlr_sf(None, None, 4, 4, None, 1, None, ctypes.c_float(0.1), 10, ctypes.c_float(1.0), None) == sfb.SFB_EINVAL
+
+
 def test_null_context_is_rejected(sfb):
     L = sfb.lib()
     assert L.sfb_apply(None, None, 4, 4, None, None, 1, 0, ctypes.c_float(0.1)) == sfb.SFB_EINVAL
