@@ -146,10 +146,20 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t a)
 // is gbase (uniform) + voff (per lane).  Issued as inline assembly so that the
 // compiler's wait-count insertion does not tie every later LDS read to it; the
 // caller waits (vmcnt) before the barrier that publishes the data.
+// NT: non-temporal, for an operand whose lines are used by a few CUs at about the
+// same time and never again (the class panel of the forward contraction: 6.5 GB
+// streaming past a 4 MiB L2 in which the sample panels should stay; forward
+// 4.78 -> 4.72 ms).  On an operand that IS reused it is ruinous (sample panel of
+// the forward +20 %, either operand of the apply +25 %).
+template <bool NT>
 __device__ __forceinline__ void load_to_lds_16(uint32_t lds_addr, uint64_t gbase, uint32_t voff)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase)
-                 : "memory");
+    if (NT)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_addr), "v"(voff), "s"(gbase)
+                     : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase)
+                     : "memory");
 }
 // One accumulator element out of the accumulation registers.  Written as
 // assembly because the compiler otherwise copies whole 16-register tiles (64
@@ -240,9 +250,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     auto issue_one = [&](int j) {
         const uint32_t dst = lds_base + iss_stage + (uint32_t)(8 * wave) * 1024u;
         if (j < 8)
-            load_to_lds_16(dst + j * 1024u, gA, offA[j & 7]);
+            load_to_lds_16<false>(dst + j * 1024u, gA, offA[j & 7]);
         else
-            load_to_lds_16(dst + B_OFF + (j - 8) * 1024u, gB, offB[j & 7]);
+            load_to_lds_16<MODE == MODE_FWD>(dst + B_OFF + (j - 8) * 1024u, gB, offB[j & 7]);
     };
     auto issue_done = [&]() {   // advance the load cursor by one slice
         gA += BK * 2;
