@@ -93,7 +93,8 @@ enum Mode : int { MODE_FWD = 0, MODE_APPLY = 1, MODE_SPLIT = 2 };
 struct Params {
     const uint16_t* A;  // bf16 [M][lda], lda % 64 == 0, k zero-padded to K
     const uint16_t* B;  // bf16 [N][ldb]
-    float* C;           // [M][ldc]
+    float* C;           // [M][ldc]; forward: stored tile by tile (see c_blocked)
+    int c_blocked;      // forward: C is an array of BM x BN tiles, tile (tm, tn) at index tn * tiles_m + tm, rows of BN floats
     uint16_t* shadow;   // apply: bf16 copy of C to refresh ([M][ld_shadow]), or null; split: high plane
     uint16_t* lo;       // split: low plane ([M][ld_shadow])
     int64_t M, N, K;    // K % 64 == 0
@@ -330,12 +331,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     };
     auto epilogue_tile = [&](int64_t m0, int64_t n0, auto guard_tag) {
         constexpr bool GUARD = decltype(guard_tag)::value;
-        const auto crs = make_rsrc(MODE == MODE_SPLIT ? p.C : p.C + (m0 + wm0) * p.ldc + n0 + wn0);
+        const auto crs = make_rsrc(MODE == MODE_SPLIT ? p.C
+                                   : (MODE == MODE_FWD && p.c_blocked)
+                                       ? p.C + ((n0 / BN) * p.tiles_m + m0 / BM) * (int64_t)(BM * BN) + wm0 * BN + wn0
+                                       : p.C + (m0 + wm0) * p.ldc + n0 + wn0);
         const bool has_shadow = p.shadow && !(p.dbg & 8);
         const auto srs = make_rsrc(has_shadow ? p.shadow + (m0 + wm0) * p.ld_shadow + n0 + wn0 : p.shadow);
         const auto lrs = make_rsrc(MODE == MODE_SPLIT ? p.lo + (m0 + wm0) * p.ld_shadow + n0 + wn0 : p.lo);
         const int rows_left = (int)(p.M - (m0 + wm0) < 4 * BM ? p.M - (m0 + wm0) : 4 * BM) - 4 * g;   // for this lane
-        const uint32_t row_c = (uint32_t)p.ldc * 4u, row_s = (uint32_t)p.ld_shadow * 2u;
+        const uint32_t row_c = (MODE == MODE_FWD && p.c_blocked) ? (uint32_t)BN * 4u : (uint32_t)p.ldc * 4u;
+        const uint32_t row_s = (uint32_t)p.ld_shadow * 2u;
         const uint32_t lane_c = (uint32_t)(4 * g) * row_c + (uint32_t)l32 * 16u;
         const uint32_t lane_s = (uint32_t)(4 * g) * row_s + (uint32_t)l32 * 8u;
         const bool col_ok = !GUARD || (n0 + wn0 + 4 * l32 < p.N);   // N % 4 == 0: all four columns or none
@@ -711,11 +716,15 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
     p.A = X_aligned; p.lda = pitch; p.M = B;
     p.B = W_shadow; p.ldb = pitch; p.N = J;
     p.C = Z; p.ldc = J;
+    p.c_blocked = 1;             // logits tile by tile: a workgroup writes 256 KB in one piece (see mlr_logits_floats)
     p.K = pitch;
     p.group_m = 0;               // all batch tiles of one class tile are neighbours (they share the W tile)
     p.dbg = g_forward_dbg;
     return launch<MODE_FWD>(p, stream);
 }
+
+// Floats of the tile-blocked logits array of launch_mlr_forward_bf16.
+int64_t mlr_logits_floats(int64_t B, int64_t J) { return ((B + BM - 1) / BM) * ((J + BN - 1) / BN) * (int64_t)(BM * BN); }
 
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D) { return (J + D) * bf16_pitch(N) * 2; }
 

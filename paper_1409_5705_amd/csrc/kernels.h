@@ -48,7 +48,10 @@ int64_t gemm_f32_partial_bytes(int64_t M, int64_t N, int64_t K);
 int64_t bf16_pitch(int64_t cols);
 // shadow[j][0..pitch) = bf16(W[j][0..D)), zero padded; pitch = bf16_pitch(D).
 hipError_t launch_shadow_from_w(const float* W, uint16_t* shadow, int64_t J, int64_t D, hipStream_t stream);
-// Z[b][j] = sum_d X[b][d] * shadow[j][d];  X bf16 [B][D], Z fp32 [B][J].
+// z(b, j) = sum_d X[b][d] * shadow[j][d];  X bf16 [B][D].  The logits are stored tile by tile:
+// Z is an array of 256 x 256 tiles (mlr_logits_floats(B, J) floats), tile (b / 256, j / 256) at index
+// (j / 256) * ceil(B / 256) + b / 256, rows of 256 floats inside a tile; launch_mlr_softmax(..., blocked_rows = B)
+// reads that layout.
 // X_aligned: scratch for the aligned copy of X, B * bf16_pitch(D) elements.
 // X == nullptr: X_aligned already holds the samples (rows zero padded to the pitch).
 hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, float* Z, uint16_t* X_aligned,
@@ -57,6 +60,7 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
 // Two steps: launch_apply_bf16_transpose writes U^T and V^T into `workspace`
 // (apply_bf16_workspace_bytes, 256-byte aligned), launch_apply_bf16 consumes them.
 // W_shadow (nullable): bf16 copy of W, refreshed with the new values.
+int64_t mlr_logits_floats(int64_t B, int64_t J);
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D);
 // coef (nullable, device, N floats): V^T is written as bf16(coef[i] * V[i][d]).
 // V == nullptr: only U^T is written; the caller fills V^T, D rows of
@@ -91,8 +95,9 @@ hipError_t launch_csr_check(const int64_t* indptr, const int32_t* indices, int64
 // Row-wise kernels.
 // ---------------------------------------------------------------------------
 // U[i][j] = exp(Z[i][j] - max_i) / sum_i - [j == y[i]];  out_bf16 selects the U dtype.
+// blocked: Z is the tile-blocked array written by launch_mlr_forward_bf16 instead of a row-major [B][J].
 hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool out_bf16,
-                              int64_t B, int64_t J, hipStream_t stream);
+                              int64_t B, int64_t J, hipStream_t stream, bool blocked = false);
 // V = X - Y (elementwise, n elements).
 hipError_t launch_diff(const float* X, const float* Y, float* V, int64_t n, hipStream_t stream);
 // DML coefficient: d = ||Q_i||^2; c = +2 (sim>0), -2 (sim<=0 and d<margin), else 0; U_i = c Q_i.

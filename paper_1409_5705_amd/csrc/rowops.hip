@@ -71,29 +71,44 @@ __device__ __forceinline__ void online_update(float& m, float& s, const floatx4 
     m = mn;
 }
 
+// tiles_m > 0: Z is not row-major but an array of 256 x 256 tiles, tile (row / 256, j / 256) at index
+// (j / 256) * tiles_m + row / 256 (the layout the bf16 forward contraction writes: one piece per workgroup).
 template <int NT, bool OUT_BF16>
 __global__ __launch_bounds__(NT) void mlr_softmax_kernel(const float* __restrict__ Z, const int32_t* __restrict__ y,
-                                                         void* __restrict__ Uv, int64_t J, int vec)
+                                                         void* __restrict__ Uv, int64_t J, int vec, int64_t tiles_m)
 {
     __shared__ float sm[NT / 64];
     const int64_t row = blockIdx.x;
-    const float* z = Z + row * J;
-    const floatx4* z4 = reinterpret_cast<const floatx4*>(z);
+    const bool blocked = tiles_m > 0;
+    const float* z = blocked ? Z + (row / 256) * 65536 + (row % 256) * 256 : Z + row * J;
+    const int64_t tile_stride = tiles_m * 65536;          // floats from a tile to the next one along j
+    struct View {   // logits of this row by class index (at1) or by group of four classes (at4)
+        const float* z;
+        int64_t ts;
+        bool blocked;
+        __device__ floatx4 at4(int64_t q) const
+        {
+            const int64_t o = blocked ? (q >> 6) * (ts >> 2) + (q & 63) : q;
+            return reinterpret_cast<const floatx4*>(z)[o];
+        }
+        __device__ float at1(int64_t j) const { return z[blocked ? (j >> 8) * ts + (j & 255) : j]; }
+    };
+    const View zv = {z, tile_stride, blocked};
     const int tid = threadIdx.x;
     const int64_t J4 = vec ? J / 4 : 0;
 
     float m = -INFINITY, s = 0.f;
     int64_t q = tid;
     for (; q + 3 * NT < J4; q += 4 * NT) {
-        const floatx4 a = z4[q], b = z4[q + NT], c = z4[q + 2 * NT], d = z4[q + 3 * NT];
+        const floatx4 a = zv.at4(q), b = zv.at4(q + NT), c = zv.at4(q + 2 * NT), d = zv.at4(q + 3 * NT);
         online_update(m, s, a);
         online_update(m, s, b);
         online_update(m, s, c);
         online_update(m, s, d);
     }
-    for (; q < J4; q += NT) online_update(m, s, z4[q]);
+    for (; q < J4; q += NT) online_update(m, s, zv.at4(q));
     for (int64_t j = J4 * 4 + tid; j < J; j += NT) {
-        const float v = z[j], mn = fmaxf(m, v);
+        const float v = zv.at1(j), mn = fmaxf(m, v);
         s = s * expf(m - mn) + expf(v - mn);
         m = mn;
     }
@@ -118,15 +133,15 @@ __global__ __launch_bounds__(NT) void mlr_softmax_kernel(const float* __restrict
     };
     q = tid;
     for (; q + 3 * NT < J4; q += 4 * NT) {
-        const floatx4 a = z4[q], b = z4[q + NT], c = z4[q + 2 * NT], d = z4[q + 3 * NT];
+        const floatx4 a = zv.at4(q), b = zv.at4(q + NT), c = zv.at4(q + 2 * NT), d = zv.at4(q + 3 * NT);
         emit(q, a);
         emit(q + NT, b);
         emit(q + 2 * NT, c);
         emit(q + 3 * NT, d);
     }
-    for (; q < J4; q += NT) emit(q, z4[q]);
+    for (; q < J4; q += NT) emit(q, zv.at4(q));
     for (int64_t j = J4 * 4 + tid; j < J; j += NT) {
-        const float p = expf(z[j] - M) * inv - ((j == lab) ? 1.0f : 0.0f);
+        const float p = expf(zv.at1(j) - M) * inv - ((j == lab) ? 1.0f : 0.0f);
         if (OUT_BF16) {
             reinterpret_cast<uint16_t*>(Uv)[row * J + j] = (uint16_t)(pack_bf16(p, 0.f) & 0xffffu);
         } else {
@@ -350,23 +365,24 @@ unsigned grid_for(int64_t n)
 }  // namespace
 
 hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool out_bf16, int64_t B, int64_t J,
-                              hipStream_t stream)
+                              hipStream_t stream, bool blocked)
 {
     if (B <= 0 || J <= 0) return hipSuccess;
     // Vector path: rows of Z (and of U) must start 16-byte (8-byte for bf16 U) aligned.
     const int vec = (J % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0) &&
                     (reinterpret_cast<uintptr_t>(U) % 16 == 0);
     const dim3 grid((unsigned)B);
+    const int64_t tiles_m = blocked ? (B + 255) / 256 : 0;
     if (J > 16384) {
         if (out_bf16)
-            hipLaunchKernelGGL((mlr_softmax_kernel<1024, true>), grid, dim3(1024), 0, stream, Z, y, U, J, vec);
+            hipLaunchKernelGGL((mlr_softmax_kernel<1024, true>), grid, dim3(1024), 0, stream, Z, y, U, J, vec, tiles_m);
         else
-            hipLaunchKernelGGL((mlr_softmax_kernel<1024, false>), grid, dim3(1024), 0, stream, Z, y, U, J, vec);
+            hipLaunchKernelGGL((mlr_softmax_kernel<1024, false>), grid, dim3(1024), 0, stream, Z, y, U, J, vec, tiles_m);
     } else {
         if (out_bf16)
-            hipLaunchKernelGGL((mlr_softmax_kernel<256, true>), grid, dim3(256), 0, stream, Z, y, U, J, vec);
+            hipLaunchKernelGGL((mlr_softmax_kernel<256, true>), grid, dim3(256), 0, stream, Z, y, U, J, vec, tiles_m);
         else
-            hipLaunchKernelGGL((mlr_softmax_kernel<256, false>), grid, dim3(256), 0, stream, Z, y, U, J, vec);
+            hipLaunchKernelGGL((mlr_softmax_kernel<256, false>), grid, dim3(256), 0, stream, Z, y, U, J, vec, tiles_m);
     }
     return hipGetLastError();
 }

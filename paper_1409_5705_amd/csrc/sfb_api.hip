@@ -249,8 +249,8 @@ int64_t sfb_workspace_bytes(int32_t model, int64_t J, int64_t D, const sfb_batch
     const int64_t B = batch->B;
     switch (model) {
         case SFB_MLR:
-            if (batch->in_dtype == SFB_BF16)   // logits, aligned copy of X, bf16 copy of W
-                return round_up(B * J * 4) + round_up(B * sfb::bf16_pitch(D) * 2) + sfb_shadow_bytes(J, D);
+            if (batch->in_dtype == SFB_BF16)   // logits (tile-blocked), aligned copy of X, bf16 copy of W
+                return round_up(sfb::mlr_logits_floats(B, J) * 4) + round_up(B * sfb::bf16_pitch(D) * 2) + sfb_shadow_bytes(J, D);
             return round_up(B * J * 4) + round_up(sfb::gemm_f32_partial_bytes(B, J, D));   // logits, k-split scratch
         case SFB_DML:
             return round_up(B * J * 4) + round_up(sfb::gemm_f32_partial_bytes(B, J, D));   // projections Q[B][K], k-split scratch
@@ -388,7 +388,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
             SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, st));
             SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, false, B, J, st));
         } else {
-            uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + round_up(B * J * 4));
+            uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + round_up(sfb::mlr_logits_floats(B, J) * 4));
             const uint16_t* Wb = ctx->shadow_buf;
             if (!has_shadow) {   // no working copy attached: make one for this call
                 uint16_t* tmp = Xa + round_up(B * sfb::bf16_pitch(D) * 2) / 2;
@@ -397,7 +397,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
             }
             SFB_RUN(KID_FORWARD_BF16,
                     sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), Wb, Z, Xa, B, J, D, st));
-            SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st));
+            SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true));
         }
         if (V && V != batch->X)
             SFB_RUN(KID_COPY, hipMemcpyAsync(V, batch->X, (size_t)(B * D * esz), hipMemcpyDeviceToDevice, st));
@@ -617,7 +617,7 @@ int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb
         return SFB_OK;
     }
     const int64_t pitch = sfb::bf16_pitch(D);
-    uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + round_up(B * J * 4));
+    uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + round_up(sfb::mlr_logits_floats(B, J) * 4));
     const uint16_t* Wb = ctx->shadow_buf;
     if (!has_shadow) {
         uint16_t* tmp = Xa + round_up(B * pitch * 2) / 2;
@@ -627,7 +627,7 @@ int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb
     SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xa, 0u, B * pitch / 2, st));
     SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, true, nullptr, Xa, B, D, X->nnz, pitch, 1, st));
     SFB_RUN(KID_FORWARD_BF16, sfb::launch_mlr_forward_bf16(nullptr, Wb, Z, Xa, B, J, D, st));
-    SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st));
+    SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true));
     return SFB_OK;
 }
 
