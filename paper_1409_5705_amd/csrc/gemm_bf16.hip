@@ -96,7 +96,7 @@ struct Params {
     float* C;           // [M][ldc]; forward: stored tile by tile (see c_blocked)
     int c_blocked;      // forward: C is an array of BM x BN tiles, tile (tm, tn) at index tn * tiles_m + tm, rows of BN floats
     uint16_t* shadow;   // apply: bf16 copy of C to refresh ([M][ld_shadow]), or null; split: high plane
-    uint16_t* lo;       // split: low plane ([M][ld_shadow])
+    uint16_t* lo;       // split: low plane, stored tile by tile (BM x BN tiles, tile (tm, tn) at index tm * tiles_n + tn)
     int64_t M, N, K;    // K % 64 == 0
     int64_t lda, ldb, ldc, ld_shadow;
     float eta;
@@ -337,7 +337,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                                        : p.C + (m0 + wm0) * p.ldc + n0 + wn0);
         const bool has_shadow = p.shadow && !(p.dbg & 8);
         const auto srs = make_rsrc(has_shadow ? p.shadow + (m0 + wm0) * p.ld_shadow + n0 + wn0 : p.shadow);
-        const auto lrs = make_rsrc(MODE == MODE_SPLIT ? p.lo + (m0 + wm0) * p.ld_shadow + n0 + wn0 : p.lo);
+        const auto lrs = make_rsrc(MODE == MODE_SPLIT
+                                       ? p.lo + ((m0 / BM) * p.tiles_n + n0 / BN) * (int64_t)(BM * BN) + wm0 * BN + wn0
+                                       : p.lo);
+        const uint32_t row_l = (uint32_t)BN * 2u, lane_l = (uint32_t)(4 * g) * row_l + (uint32_t)l32 * 8u;
         const int rows_left = (int)(p.M - (m0 + wm0) < 4 * BM ? p.M - (m0 + wm0) : 4 * BM) - 4 * g;   // for this lane
         const uint32_t row_c = (MODE == MODE_FWD && p.c_blocked) ? (uint32_t)BN * 4u : (uint32_t)p.ldc * 4u;
         const uint32_t row_s = (uint32_t)p.ld_shadow * 2u;
@@ -358,7 +361,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                 if (col_ok && (!GUARD || dr < rows_left)) {
                     if (MODE == MODE_SPLIT) {   // four columns of the high plane, then of the low plane
                         const u32x2 h = __builtin_amdgcn_raw_buffer_load_b64(srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
-                        const u32x2 l = __builtin_amdgcn_raw_buffer_load_b64(lrs, lane_s, (uint32_t)dr * row_s, C_POLICY);
+                        const u32x2 l = __builtin_amdgcn_raw_buffer_load_b64(lrs, lane_l, (uint32_t)dr * row_l, C_POLICY);
                         const uint32_t h0 = h[0], h1 = h[1], l0 = l[0], l1 = l[1];
                         dst[e] = u32x4{h0, h1, l0, l1};
                     } else {
@@ -395,7 +398,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                         const u32x2 oh = {split_hi(n0f) | (split_hi(n1f) << 16), split_hi(n2f) | (split_hi(n3f) << 16)};
                         const u32x2 ol = {split_lo(n0f) | (split_lo(n1f) << 16), split_lo(n2f) | (split_lo(n3f) << 16)};
                         __builtin_amdgcn_raw_buffer_store_b64(oh, srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
-                        __builtin_amdgcn_raw_buffer_store_b64(ol, lrs, lane_s, (uint32_t)dr * row_s, C_POLICY);
+                        __builtin_amdgcn_raw_buffer_store_b64(ol, lrs, lane_l, (uint32_t)dr * row_l, C_POLICY);
                     } else {
                         const uint32_t o0 = w[q % EPD][e][0], o1 = w[q % EPD][e][1], o2 = w[q % EPD][e][2],
                                        o3 = w[q % EPD][e][3];
@@ -598,9 +601,15 @@ __global__ __launch_bounds__(256) void pad_rows_bf16_kernel(const SrcT* __restri
 }
 
 // W[J][D] fp32 -> the two planes ([J][pitch], columns D.. zero), 8 elements a thread; and back.
+// Element (r, c) of the low plane: the plane is an array of BM x BN tiles in row-major tile order.
+__device__ __forceinline__ int64_t split_lo_index(int64_t r, int64_t c, int64_t tiles_n)
+{
+    return ((r / BM) * tiles_n + c / BN) * (int64_t)(BM * BN) + (r % BM) * BN + c % BN;
+}
+
 __global__ __launch_bounds__(256) void split_from_w_kernel(const float* __restrict__ W, uint16_t* __restrict__ hi,
                                                            uint16_t* __restrict__ lo, int64_t rows, int64_t cols,
-                                                           int64_t pitch)
+                                                           int64_t pitch, int64_t tiles_n)
 {
     const int64_t chunks = pitch / 8, total = rows * chunks;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
@@ -616,19 +625,19 @@ __global__ __launch_bounds__(256) void split_from_w_kernel(const float* __restri
                       split_lo(b0) | (split_lo(b1) << 16), split_lo(b2) | (split_lo(b3) << 16)};
         }
         *reinterpret_cast<u32x4*>(hi + r * pitch + c) = h;
-        *reinterpret_cast<u32x4*>(lo + r * pitch + c) = l;
+        if (c < cols) *reinterpret_cast<u32x4*>(lo + split_lo_index(r, c, tiles_n)) = l;
     }
 }
 
 __global__ __launch_bounds__(256) void w_from_split_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
                                                            float* __restrict__ W, int64_t rows, int64_t cols,
-                                                           int64_t pitch)
+                                                           int64_t pitch, int64_t tiles_n)
 {
     const int64_t chunks = cols / 8, total = rows * chunks;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
         const int64_t r = idx / chunks, c = (idx % chunks) * 8;
         const u32x4 h = *reinterpret_cast<const u32x4*>(hi + r * pitch + c);
-        const u32x4 l = *reinterpret_cast<const u32x4*>(lo + r * pitch + c);
+        const u32x4 l = *reinterpret_cast<const u32x4*>(lo + split_lo_index(r, c, tiles_n));
         const uint32_t h0 = h[0], h1 = h[1], h2 = h[2], h3 = h[3], l0 = l[0], l1 = l[1], l2 = l[2], l3 = l[3];
         const floatx4 a = {split_join(h0 & 0xffffu, l0 & 0xffffu), split_join(h0 >> 16, l0 >> 16),
                            split_join(h1 & 0xffffu, l1 & 0xffffu), split_join(h1 >> 16, l1 >> 16)};
@@ -726,6 +735,9 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
 // Floats of the tile-blocked logits array of launch_mlr_forward_bf16.
 int64_t mlr_logits_floats(int64_t B, int64_t J) { return ((B + BM - 1) / BM) * ((J + BN - 1) / BN) * (int64_t)(BM * BN); }
 
+// Bytes of the low plane of a J x D matrix kept as two planes (whole 256 x 256 tiles).
+int64_t split_lo_bytes(int64_t J, int64_t D) { return ((J + BM - 1) / BM) * ((D + BN - 1) / BN) * (int64_t)(BM * BN) * 2; }
+
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D) { return (J + D) * bf16_pitch(N) * 2; }
 
 uint16_t* apply_bf16_vt(void* workspace, int64_t N, int64_t J)
@@ -752,7 +764,7 @@ hipError_t launch_split_from_w(const float* W, uint16_t* hi, uint16_t* lo, int64
 {
     if (J <= 0 || D <= 0) return hipSuccess;
     const int64_t pitch = bf16_pitch(D);
-    hipLaunchKernelGGL(split_from_w_kernel, dim3(grid_for(J * (pitch / 8))), dim3(256), 0, stream, W, hi, lo, J, D, pitch);
+    hipLaunchKernelGGL(split_from_w_kernel, dim3(grid_for(J * (pitch / 8))), dim3(256), 0, stream, W, hi, lo, J, D, pitch, (D + BN - 1) / BN);
     return hipGetLastError();
 }
 
@@ -760,7 +772,7 @@ hipError_t launch_w_from_split(const uint16_t* hi, const uint16_t* lo, float* W,
 {
     if (J <= 0 || D <= 0) return hipSuccess;
     hipLaunchKernelGGL(w_from_split_kernel, dim3(grid_for(J * (D / 8))), dim3(256), 0, stream, hi, lo, W, J, D,
-                       bf16_pitch(D));
+                       bf16_pitch(D), (D + BN - 1) / BN);
     return hipGetLastError();
 }
 

@@ -72,7 +72,10 @@ hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, con
 // to bf16) and W_lo the low one; both are updated and the fp32 array W is not touched.
 hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64_t N, int64_t J, int64_t D, float eta,
                              const void* workspace, hipStream_t stream);
-// fp32 W[J][D] <-> planes hi, lo ([J][bf16_pitch(D)] each): bits = (hi << 16) + sign_extend(lo).
+// fp32 W[J][D] <-> planes hi ([J][bf16_pitch(D)], the layout of the bf16 working copy) and lo (split_lo_bytes(J, D)
+// bytes: 256 x 256 tiles in row-major tile order, so that a workgroup of the apply reads and writes one piece):
+// bits = (hi << 16) + sign_extend(lo).
+int64_t split_lo_bytes(int64_t J, int64_t D);
 hipError_t launch_split_from_w(const float* W, uint16_t* hi, uint16_t* lo, int64_t J, int64_t D, hipStream_t stream);
 hipError_t launch_w_from_split(const uint16_t* hi, const uint16_t* lo, float* W, int64_t J, int64_t D, hipStream_t stream);
 // Timing experiments (benchmark sweeps): variant / 100 = debug bits; -1 = normal.

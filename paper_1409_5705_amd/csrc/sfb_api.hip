@@ -294,7 +294,7 @@ int sfb_shadow_detach(sfb_ctx* ctx)
 int64_t sfb_split_bytes(int64_t J, int64_t D)
 {
     const int64_t plane = sfb_shadow_bytes(J, D);
-    return plane < 0 ? plane : 2 * plane;
+    return plane < 0 ? plane : plane + round_up(sfb::split_lo_bytes(J, D));
 }
 
 int sfb_split_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* dev_ptr, int64_t bytes)
@@ -304,7 +304,7 @@ int sfb_split_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* d
         return SFB_EINVAL;   // something else is attached (the same matrix in split form may be refreshed)
     const int64_t plane = sfb_shadow_bytes(J, D);
     if (plane < 0) return SFB_EINVAL;
-    if (bytes < 2 * plane) return SFB_ENOWS;
+    if (bytes < sfb_split_bytes(J, D)) return SFB_ENOWS;
     if (reinterpret_cast<uintptr_t>(dev_ptr) % ALIGN != 0) return SFB_EINVAL;
     SFB_TRY(hipSetDevice(ctx->device));
     uint16_t* hi = static_cast<uint16_t*>(dev_ptr);
