@@ -54,8 +54,10 @@ hipError_t launch_shadow_from_w(const float* W, uint16_t* shadow, int64_t J, int
 // reads that layout.
 // X_aligned: scratch for the aligned copy of X, B * bf16_pitch(D) elements.
 // X == nullptr: X_aligned already holds the samples (rows zero padded to the pitch).
+// w_blocked: W_shadow is the high plane of a matrix kept as two planes (launch_split_from_w) instead of a
+// row-major working copy.
 hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, float* Z, uint16_t* X_aligned,
-                                   int64_t B, int64_t J, int64_t D, hipStream_t stream);
+                                   int64_t B, int64_t J, int64_t D, hipStream_t stream, bool w_blocked = false);
 // W[j][d] -= eta * sum_i U[i][j] * V[i][d];  U bf16 [N][J], V bf16 [N][D], W fp32 [J][D].
 // Two steps: launch_apply_bf16_transpose writes U^T and V^T into `workspace`
 // (apply_bf16_workspace_bytes, 256-byte aligned), launch_apply_bf16 consumes them.
@@ -72,9 +74,11 @@ hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, con
 // to bf16) and W_lo the low one; both are updated and the fp32 array W is not touched.
 hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64_t N, int64_t J, int64_t D, float eta,
                              const void* workspace, hipStream_t stream);
-// fp32 W[J][D] <-> planes hi ([J][bf16_pitch(D)], the layout of the bf16 working copy) and lo (split_lo_bytes(J, D)
-// bytes: 256 x 256 tiles in row-major tile order, so that a workgroup of the apply reads and writes one piece):
+// fp32 W[J][D] <-> planes hi (split_hi_bytes(J, D) bytes: blocks of 256 rows x 64 columns, the k-slices of the
+// forward contraction's row tiles, each 32 KB in one piece; columns D.. of the pitch are zero) and lo
+// (split_lo_bytes(J, D) bytes: 256 x 256 tiles in row-major tile order, one piece per workgroup of the apply):
 // bits = (hi << 16) + sign_extend(lo).
+int64_t split_hi_bytes(int64_t J, int64_t D);
 int64_t split_lo_bytes(int64_t J, int64_t D);
 hipError_t launch_split_from_w(const float* W, uint16_t* hi, uint16_t* lo, int64_t J, int64_t D, hipStream_t stream);
 hipError_t launch_w_from_split(const uint16_t* hi, const uint16_t* lo, float* W, int64_t J, int64_t D, hipStream_t stream);

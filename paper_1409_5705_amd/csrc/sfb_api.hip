@@ -294,7 +294,7 @@ int sfb_shadow_detach(sfb_ctx* ctx)
 int64_t sfb_split_bytes(int64_t J, int64_t D)
 {
     const int64_t plane = sfb_shadow_bytes(J, D);
-    return plane < 0 ? plane : plane + round_up(sfb::split_lo_bytes(J, D));
+    return plane < 0 ? plane : round_up(sfb::split_hi_bytes(J, D)) + round_up(sfb::split_lo_bytes(J, D));
 }
 
 int sfb_split_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* dev_ptr, int64_t bytes)
@@ -308,7 +308,7 @@ int sfb_split_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* d
     if (reinterpret_cast<uintptr_t>(dev_ptr) % ALIGN != 0) return SFB_EINVAL;
     SFB_TRY(hipSetDevice(ctx->device));
     uint16_t* hi = static_cast<uint16_t*>(dev_ptr);
-    uint16_t* lo = hi + plane / 2;
+    uint16_t* lo = hi + round_up(sfb::split_hi_bytes(J, D)) / 2;
     SFB_RUN(KID_SHADOW, sfb::launch_split_from_w(W, hi, lo, J, D, ctx->stream));
     ctx->shadow_W = W;
     ctx->shadow_buf = hi;
@@ -396,7 +396,8 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
                 Wb = tmp;
             }
             SFB_RUN(KID_FORWARD_BF16,
-                    sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), Wb, Z, Xa, B, J, D, st));
+                    sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), Wb, Z, Xa, B, J, D, st,
+                                                 is_split(ctx, W)));
             SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true));
         }
         if (V && V != batch->X)
@@ -626,7 +627,7 @@ int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb
     }
     SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xa, 0u, B * pitch / 2, st));
     SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, true, nullptr, Xa, B, D, X->nnz, pitch, 1, st));
-    SFB_RUN(KID_FORWARD_BF16, sfb::launch_mlr_forward_bf16(nullptr, Wb, Z, Xa, B, J, D, st));
+    SFB_RUN(KID_FORWARD_BF16, sfb::launch_mlr_forward_bf16(nullptr, Wb, Z, Xa, B, J, D, st, is_split(ctx, W)));
     SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true));
     return SFB_OK;
 }

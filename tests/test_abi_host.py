@@ -75,8 +75,8 @@ def test_workspace_bytes_logic(sfb):
 
 def test_sizes_of_the_later_entry_points(sfb):
     L = sfb.lib()
-    # high plane = a bf16 working copy, low plane = whole 256 x 256 tiles of 16-bit words
-    assert L.sfb_split_bytes(104, 72) == L.sfb_shadow_bytes(104, 72) + 256 * 256 * 2 and L.sfb_split_bytes(104, 70) == sfb.SFB_EINVAL
+    # high plane: whole blocks of 256 rows x the 128-column pitch; low plane: whole 256 x 256 tiles of 16-bit words
+    assert L.sfb_split_bytes(104, 72) == 256 * 128 * 2 + 256 * 256 * 2 and L.sfb_split_bytes(104, 70) == sfb.SFB_EINVAL
     # CSR: bf16 needs no more than the dense call, fp32 a dense copy of X (or V) more
     b16 = _batch(sfb, B=8, in_dtype=1, sf_dtype=1)
     assert L.sfb_mlr_sf_csr_workspace_bytes(104, 72, 8, 1) == L.sfb_workspace_bytes(sfb.SFB_MLR, 104, 72, ctypes.byref(b16))
