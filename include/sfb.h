@@ -101,10 +101,13 @@ int sfb_shadow_detach(sfb_ctx* ctx);
 /*
  * Optional split storage of one parameter matrix, for the bf16 multiclass-logistic
  * path (instead of a working copy, not in addition to one).  The fp32 word of every
- * element is kept as two 16-bit halves in two separate planes with 128-byte-aligned
- * rows: hi = (bits + 0x8000) >> 16, which is the value rounded to bf16 (to nearest,
- * ties away from zero), and lo = bits & 0xffff; bits = (hi << 16) + sign_extend(lo)
- * modulo 2^32, exactly.  The forward contraction reads the hi plane as its bf16
+ * element is kept as two 16-bit halves in two separate planes: hi = (bits + 0x8000)
+ * >> 16, which is the value rounded to bf16 (to nearest, ties away from zero), and
+ * lo = bits & 0xffff; bits = (hi << 16) + sign_extend(lo) modulo 2^32, exactly.  Inside
+ * the buffer the planes are laid out for the two kernels that stream them (hi in
+ * blocks of 256 rows x 64 columns, lo in tiles of 256 x 256, each block one
+ * contiguous piece); the layout is the library's business, the caller only provides
+ * sfb_split_bytes bytes.  The forward contraction reads the hi plane as its bf16
  * operand; sfb_apply reads and writes both planes, i.e. the same 8 bytes per
  * element as a read-modify-write of the fp32 array, with the same fp32 arithmetic
  * and the same resulting bits, but without the third write that keeps a separate
