@@ -94,6 +94,7 @@ struct Params {
     const uint16_t* A;  // bf16 [M][lda], lda % 64 == 0, k zero-padded to K
     const uint16_t* B;  // bf16 [N][ldb], or (b_blocked) blocks of BN rows x BK columns, block (n / BN, k / BK) at index (n / BN) * (K / BK) + k / BK
     int b_blocked;
+    int a_blocked;      // the same for A (blocks of BM rows x BK columns)
     float* C;           // [M][ldc]; forward: stored tile by tile (see c_blocked)
     int c_blocked;      // forward: C is an array of BM x BN tiles, tile (tm, tn) at index tn * tiles_m + tm, rows of BN floats
     uint16_t* shadow;   // apply: bf16 copy of C to refresh ([M][ld_shadow]), or null; split: high plane
@@ -225,8 +226,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     // 8b + (l >> 3), i.e. fetches chunk (l & 7) ^ swz(row).  Rows past the end of
     // the matrix are clamped to its last row: they only feed accumulators that
     // are never stored; k is zero-padded.
-    const uint32_t pitchA = (uint32_t)p.lda * 2u, pitchB = p.b_blocked ? (uint32_t)BK * 2u : (uint32_t)p.ldb * 2u;
-    const uint64_t stepB = p.b_blocked ? (uint64_t)BN * BK * 2 : (uint64_t)BK * 2;   // bytes from a k-slice of B to the next
+    const uint32_t pitchA = p.a_blocked ? (uint32_t)BK * 2u : (uint32_t)p.lda * 2u;
+    const uint32_t pitchB = p.b_blocked ? (uint32_t)BK * 2u : (uint32_t)p.ldb * 2u;
+    const uint64_t stepA = p.a_blocked ? (uint64_t)BM * BK * 2 : (uint64_t)BK * 2;   // bytes from a k-slice to the next
+    const uint64_t stepB = p.b_blocked ? (uint64_t)BN * BK * 2 : (uint64_t)BK * 2;
     uint32_t offA[8], offB[8];
     uint64_t gA = 0, gB = 0;           // address of (row 0, current k-slice) of the tile being loaded
     int64_t iss_q = 0, iss_k = 0;
@@ -234,7 +237,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     auto enter_tile = [&](int64_t ordinal) {
         int64_t m0, n0;
         tile_origin(ordinal, m0, n0);
-        gA = uniform64(reinterpret_cast<uint64_t>(p.A) + (uint64_t)(m0 * p.lda * 2));
+        gA = uniform64(reinterpret_cast<uint64_t>(p.A) +
+                       (p.a_blocked ? (uint64_t)(m0 / BM) * (uint64_t)nk * stepA : (uint64_t)(m0 * p.lda * 2)));
         gB = uniform64(reinterpret_cast<uint64_t>(p.B) +
                        (p.b_blocked ? (uint64_t)(n0 / BN) * (uint64_t)nk * stepB : (uint64_t)(n0 * p.ldb * 2)));
         const int lastA = (int)(p.M - m0 < BM ? p.M - m0 : BM) - 1;
@@ -259,7 +263,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             load_to_lds_16<MODE == MODE_FWD>(dst + B_OFF + (j - 8) * 1024u, gB, offB[j & 7]);
     };
     auto issue_done = [&]() {   // advance the load cursor by one slice
-        gA += BK * 2;
+        gA += stepA;
         gB += stepB;
         iss_stage ^= STAGE;
         ++iss_q;
@@ -268,7 +272,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             if (iss_q < S) {
                 enter_tile(iss_q / nk);
             } else {   // past the last slice: stay on the last tile (such loads are never read)
-                gA -= (uint64_t)nk * (BK * 2);
+                gA -= (uint64_t)nk * stepA;
                 gB -= (uint64_t)nk * stepB;
             }
         }
@@ -538,8 +542,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     wait_all_vmem();   // no direct load may be in flight when the workgroup's LDS is released
 }
 
-// src[rows_src][cols] (bf16, row-major) -> dst[cols][pitch]; source rows
-// rows_src..pitch-1 are taken as zero.  cols % 8 == 0, pitch % 64 == 0.
+// src[rows_src][cols] (bf16, row-major) -> dst = its transpose [cols][pitch] in the blocked operand layout of
+// sf_gemm_kernel; source rows rows_src..pitch-1 are taken as zero.  cols % 8 == 0, pitch % 64 == 0.
 // 64x64 tiles through LDS, 256 threads, 16-byte global accesses on both sides
 // (8 lanes cover one 128-byte row segment).
 // coef (nullable): source row k is scaled by coef[k] (product in fp32, rounded to
@@ -579,7 +583,10 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __r
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             o[i] = (uint32_t)tile[(kc + 2 * i) * LP + cr] | ((uint32_t)tile[(kc + 2 * i + 1) * LP + cr] << 16);
-        if (c < cols) *reinterpret_cast<u32x4*>(dst + c * pitch + k0 + kc) = u32x4{o[0], o[1], o[2], o[3]};
+        // (dst is stored in blocks of 256 rows x 64 columns, block (c / 256, k / 64) at index (c / 256) * (pitch / 64) + k / 64)
+        if (c < cols)
+            *reinterpret_cast<u32x4*>(dst + ((c / 256) * (pitch / 64) + k0 / 64) * 16384 + (c % 256) * 64 + kc) =
+                u32x4{o[0], o[1], o[2], o[3]};
     }
 }
 
@@ -756,11 +763,15 @@ int64_t split_hi_bytes(int64_t J, int64_t D) { return ((J + BM - 1) / BM) * (int
 // Bytes of the low plane of a J x D matrix kept as two planes (whole 256 x 256 tiles).
 int64_t split_lo_bytes(int64_t J, int64_t D) { return ((J + BM - 1) / BM) * ((D + BN - 1) / BN) * (int64_t)(BM * BN) * 2; }
 
-int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D) { return (J + D) * bf16_pitch(N) * 2; }
+// U^T and V^T in blocks of 256 rows x 64 columns: whole row blocks.
+int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D)
+{
+    return ((J + BM - 1) / BM * BM + (D + BN - 1) / BN * BN) * bf16_pitch(N) * 2;
+}
 
 uint16_t* apply_bf16_vt(void* workspace, int64_t N, int64_t J)
 {
-    return static_cast<uint16_t*>(workspace) + J * bf16_pitch(N);
+    return static_cast<uint16_t*>(workspace) + (J + BM - 1) / BM * BM * bf16_pitch(N);
 }
 
 hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, const float* coef, int64_t N, int64_t J,
@@ -769,7 +780,7 @@ hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, con
     if (N <= 0 || J <= 0 || D <= 0) return hipSuccess;
     const int64_t Np = bf16_pitch(N);
     uint16_t* Ut = static_cast<uint16_t*>(workspace);
-    uint16_t* Vt = Ut + J * Np;
+    uint16_t* Vt = apply_bf16_vt(workspace, N, J);
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((J + 63) / 64), (unsigned)(Np / 64)), dim3(256), 0,
                        stream, U, Ut, N, J, Np, static_cast<const float*>(nullptr));
     if (V)     // null: the caller writes V^T itself (apply_bf16_vt)
@@ -800,10 +811,11 @@ hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64
     if (N <= 0 || J <= 0 || D <= 0) return hipSuccess;
     const int64_t Np = bf16_pitch(N);
     const uint16_t* Ut = static_cast<const uint16_t*>(workspace);
-    const uint16_t* Vt = Ut + J * Np;
+    const uint16_t* Vt = apply_bf16_vt(const_cast<void*>(workspace), N, J);
     Params p = {};
     p.A = Ut; p.lda = Np; p.M = J;
     p.B = Vt; p.ldb = Np; p.N = D;
+    p.a_blocked = p.b_blocked = 1;
     p.C = W; p.ldc = D;
     p.shadow = W_shadow; p.ld_shadow = bf16_pitch(D);
     p.K = Np;

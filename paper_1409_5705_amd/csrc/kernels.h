@@ -65,8 +65,9 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
 int64_t mlr_logits_floats(int64_t B, int64_t J);
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D);
 // coef (nullable, device, N floats): V^T is written as bf16(coef[i] * V[i][d]).
-// V == nullptr: only U^T is written; the caller fills V^T, D rows of
-// bf16_pitch(N) elements at apply_bf16_vt(workspace, N, J), columns N.. zero.
+// U^T and V^T are stored in blocks of 256 rows x 64 columns (block (r / 256, k / 64) at index
+// (r / 256) * (bf16_pitch(N) / 64) + k / 64).  V == nullptr: only U^T is written; the caller fills V^T in that
+// layout at apply_bf16_vt(workspace, N, J) (round_up(D, 256) * bf16_pitch(N) elements, columns N.. zero).
 uint16_t* apply_bf16_vt(void* workspace, int64_t N, int64_t J);
 hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, const float* coef, int64_t N, int64_t J,
                                        int64_t D, void* workspace, hipStream_t stream);
@@ -89,7 +90,8 @@ void set_bf16_variant(int forward_variant, int apply_variant);
 // CSR rows (indptr int64 [rows + 1], indices int32, values fp32 or bf16).
 // ---------------------------------------------------------------------------
 // dst[r * row_stride + c * col_stride] = value (* coef[r] if coef) for every stored
-// entry (r, c); dst must have been zero-filled.  Entries outside [0, cols) and row
+// entry (r, c); dst must have been zero-filled.  col_stride = -P (P % 64 == 0) instead writes the transpose
+// [cols][P] in the blocked operand layout of the bf16 contractions (blocks of 256 rows x 64 columns).  Entries outside [0, cols) and row
 // ranges outside [0, nnz] are skipped.
 hipError_t launch_csr_scatter(const int64_t* indptr, const int32_t* indices, const void* values, bool bf16,
                               const float* coef, void* dst, int64_t rows, int64_t cols, int64_t nnz,

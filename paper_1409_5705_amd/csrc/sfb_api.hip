@@ -676,8 +676,8 @@ int sfb_apply_csr(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, c
     }
     const int64_t Np = sfb::bf16_pitch(N);
     uint16_t* Vt = sfb::apply_bf16_vt(ctx->ws, N, J);
-    SFB_RUN(KID_FILL, sfb::launch_fill_u32(Vt, 0u, D * Np / 2, st));
-    SFB_RUN(KID_CSR, sfb::launch_csr_scatter(V->indptr, V->indices, V->values, true, coef, Vt, N, D, V->nnz, 1, Np, st));
+    SFB_RUN(KID_FILL, sfb::launch_fill_u32(Vt, 0u, (D + 255) / 256 * 256 * Np / 2, st));
+    SFB_RUN(KID_CSR, sfb::launch_csr_scatter(V->indptr, V->indices, V->values, true, coef, Vt, N, D, V->nnz, 1, -Np, st));
     SFB_RUN(KID_APPLY_TRANSPOSE, sfb::launch_apply_bf16_transpose(static_cast<const uint16_t*>(U), nullptr, nullptr, N, J,
                                                                   D, ctx->ws, st));
     SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, has_shadow ? ctx->shadow_buf : nullptr,
