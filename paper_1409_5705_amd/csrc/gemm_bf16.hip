@@ -91,10 +91,8 @@ constexpr int EPD = 4;                   // epilogue: blocks of C loads in fligh
 enum Mode : int { MODE_FWD = 0, MODE_APPLY = 1, MODE_SPLIT = 2 };
 
 struct Params {
-    const uint16_t* A;  // bf16 [M][lda], lda % 64 == 0, k zero-padded to K
-    const uint16_t* B;  // bf16 [N][ldb], or (b_blocked) blocks of BN rows x BK columns, block (n / BN, k / BK) at index (n / BN) * (K / BK) + k / BK
-    int b_blocked;
-    int a_blocked;      // the same for A (blocks of BM rows x BK columns)
+    const uint16_t* A;  // bf16 in blocks of 256 rows x 64 columns (operand_index): block (m / 256, k / 64) at index (m / 256) * (K / 64) + k / 64; k zero-padded to K
+    const uint16_t* B;  // bf16, the same layout ((n / 256) * (K / 64) + k / 64)
     float* C;           // [M][ldc]; forward: stored tile by tile (see c_blocked)
     int c_blocked;      // forward: C is an array of BM x BN tiles, tile (tm, tn) at index tn * tiles_m + tm, rows of BN floats
     uint16_t* shadow;   // apply: bf16 copy of C to refresh ([M][ld_shadow]), or null; split: high plane
@@ -125,6 +123,12 @@ __device__ __forceinline__ float split_join(uint32_t hi16, uint32_t lo16)
 __device__ __forceinline__ uint32_t split_hi(float v) { return (__float_as_uint(v) + 0x8000u) >> 16; }
 __device__ __forceinline__ uint32_t split_lo(float v) { return __float_as_uint(v) & 0xffffu; }
 
+// Element (r, c) of a bf16 operand of sf_gemm_kernel (and of the high plane): blocks of BM rows x BK columns
+// (one k-slice of a row tile, 32 KB in one piece), block (r / BM, c / BK) at index (r / BM) * (pitch / BK) + c / BK.
+__device__ __forceinline__ int64_t operand_index(int64_t r, int64_t c, int64_t pitch)
+{
+    return ((r / BM) * (pitch / BK) + c / BK) * (int64_t)(BM * BK) + (r % BM) * BK + c % BK;
+}
 // Chunk-slot swizzle of tile row r: chunk c of the row sits in slot c ^ swz(r).
 // Chosen by measurement: an MFMA operand read (32 consecutive rows at chunk g,
 // 16 bytes a lane) costs 26.9 cycles with this function, as little as with
@@ -226,10 +230,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     // 8b + (l >> 3), i.e. fetches chunk (l & 7) ^ swz(row).  Rows past the end of
     // the matrix are clamped to its last row: they only feed accumulators that
     // are never stored; k is zero-padded.
-    const uint32_t pitchA = p.a_blocked ? (uint32_t)BK * 2u : (uint32_t)p.lda * 2u;
-    const uint32_t pitchB = p.b_blocked ? (uint32_t)BK * 2u : (uint32_t)p.ldb * 2u;
-    const uint64_t stepA = p.a_blocked ? (uint64_t)BM * BK * 2 : (uint64_t)BK * 2;   // bytes from a k-slice to the next
-    const uint64_t stepB = p.b_blocked ? (uint64_t)BN * BK * 2 : (uint64_t)BK * 2;
+    const uint32_t pitchA = (uint32_t)BK * 2u, pitchB = (uint32_t)BK * 2u;   // a row of a block is one 128-byte line
+    const uint64_t stepA = (uint64_t)BM * BK * 2, stepB = (uint64_t)BN * BK * 2;   // bytes from a k-slice to the next
     uint32_t offA[8], offB[8];
     uint64_t gA = 0, gB = 0;           // address of (row 0, current k-slice) of the tile being loaded
     int64_t iss_q = 0, iss_k = 0;
@@ -237,10 +239,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     auto enter_tile = [&](int64_t ordinal) {
         int64_t m0, n0;
         tile_origin(ordinal, m0, n0);
-        gA = uniform64(reinterpret_cast<uint64_t>(p.A) +
-                       (p.a_blocked ? (uint64_t)(m0 / BM) * (uint64_t)nk * stepA : (uint64_t)(m0 * p.lda * 2)));
-        gB = uniform64(reinterpret_cast<uint64_t>(p.B) +
-                       (p.b_blocked ? (uint64_t)(n0 / BN) * (uint64_t)nk * stepB : (uint64_t)(n0 * p.ldb * 2)));
+        gA = uniform64(reinterpret_cast<uint64_t>(p.A) + (uint64_t)(m0 / BM) * (uint64_t)nk * stepA);
+        gB = uniform64(reinterpret_cast<uint64_t>(p.B) + (uint64_t)(n0 / BN) * (uint64_t)nk * stepB);
         const int lastA = (int)(p.M - m0 < BM ? p.M - m0 : BM) - 1;
         const int lastB = (int)(p.N - n0 < BN ? p.N - n0 : BN) - 1;
 #pragma unroll
@@ -343,22 +343,19 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                                        ? p.C + ((n0 / BN) * p.tiles_m + m0 / BM) * (int64_t)(BM * BN) + wm0 * BN + wn0
                                        : p.C + (m0 + wm0) * p.ldc + n0 + wn0);
         const bool has_shadow = p.shadow && !(p.dbg & 8);
-        // (split: the high plane is stored as blocks of BM rows x 64 columns, see split_hi_index)
-        const auto srs = make_rsrc(MODE == MODE_SPLIT
+        // (the bf16 copy / high plane is stored in the operand layout: blocks of BM rows x 64 columns)
+        const auto srs = make_rsrc((MODE == MODE_SPLIT || has_shadow)
                                        ? p.shadow + ((m0 / BM) * (p.ld_shadow / BK) + (n0 + wn0) / BK) * (int64_t)(BM * BK) + wm0 * BK
-                                   : has_shadow ? p.shadow + (m0 + wm0) * p.ld_shadow + n0 + wn0
-                                                : p.shadow);
+                                       : p.shadow);
         const auto lrs = make_rsrc(MODE == MODE_SPLIT
                                        ? p.lo + ((m0 / BM) * p.tiles_n + n0 / BN) * (int64_t)(BM * BN) + wm0 * BN + wn0
                                        : p.lo);
         const uint32_t row_l = (uint32_t)BN * 2u, lane_l = (uint32_t)(4 * g) * row_l + (uint32_t)l32 * 8u;
         const int rows_left = (int)(p.M - (m0 + wm0) < 4 * BM ? p.M - (m0 + wm0) : 4 * BM) - 4 * g;   // for this lane
         const uint32_t row_c = (MODE == MODE_FWD && p.c_blocked) ? (uint32_t)BN * 4u : (uint32_t)p.ldc * 4u;
-        const uint32_t row_s = MODE == MODE_SPLIT ? (uint32_t)BK * 2u : (uint32_t)p.ld_shadow * 2u;
+        const uint32_t row_s = (uint32_t)BK * 2u;
         const uint32_t lane_c = (uint32_t)(4 * g) * row_c + (uint32_t)l32 * 16u;
-        const uint32_t lane_s = MODE == MODE_SPLIT
-                                    ? (uint32_t)(l32 >> 4) * (uint32_t)(BM * BK * 2) + (uint32_t)(4 * g) * row_s + (uint32_t)(l32 & 15) * 8u
-                                    : (uint32_t)(4 * g) * row_s + (uint32_t)l32 * 8u;
+        const uint32_t lane_s = (uint32_t)(l32 >> 4) * (uint32_t)(BM * BK * 2) + (uint32_t)(4 * g) * row_s + (uint32_t)(l32 & 15) * 8u;
         const bool col_ok = !GUARD || (n0 + wn0 + 4 * l32 < p.N);   // N % 4 == 0: all four columns or none
         // One block = 16 rows of one ta (8 accesses of 16 bytes per lane).  The loads
         // of the next EPD - 1 blocks are in flight while a block is combined and
@@ -585,12 +582,11 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __r
             o[i] = (uint32_t)tile[(kc + 2 * i) * LP + cr] | ((uint32_t)tile[(kc + 2 * i + 1) * LP + cr] << 16);
         // (dst is stored in blocks of 256 rows x 64 columns, block (c / 256, k / 64) at index (c / 256) * (pitch / 64) + k / 64)
         if (c < cols)
-            *reinterpret_cast<u32x4*>(dst + ((c / 256) * (pitch / 64) + k0 / 64) * 16384 + (c % 256) * 64 + kc) =
-                u32x4{o[0], o[1], o[2], o[3]};
+            *reinterpret_cast<u32x4*>(dst + operand_index(c, k0 + kc, pitch)) = u32x4{o[0], o[1], o[2], o[3]};
     }
 }
 
-// dst[r][0..pitch) = bf16(src[r][0..cols)) followed by zeros; 8 elements a thread.
+// dst(r, 0..pitch) = bf16(src[r][0..cols)) followed by zeros, in the operand layout; 8 elements a thread.
 template <typename SrcT>
 __global__ __launch_bounds__(256) void pad_rows_bf16_kernel(const SrcT* __restrict__ src, uint16_t* __restrict__ dst,
                                                             int64_t rows, int64_t cols, int64_t pitch)
@@ -612,17 +608,11 @@ __global__ __launch_bounds__(256) void pad_rows_bf16_kernel(const SrcT* __restri
                 v = *reinterpret_cast<const u32x4*>(src + r * cols + c);
             }
         }
-        *reinterpret_cast<u32x4*>(dst + r * pitch + c) = v;
+        *reinterpret_cast<u32x4*>(dst + operand_index(r, c, pitch)) = v;
     }
 }
 
 // W[J][D] fp32 -> the two planes ([J][pitch], columns D.. zero), 8 elements a thread; and back.
-// Element (r, c) of the high plane: blocks of BM rows x BK columns (one k-slice of a row tile of the forward
-// contraction, 32 KB in one piece), block (r / BM, c / BK) at index (r / BM) * (pitch / BK) + c / BK.
-__device__ __forceinline__ int64_t split_hi_index(int64_t r, int64_t c, int64_t pitch)
-{
-    return ((r / BM) * (pitch / BK) + c / BK) * (int64_t)(BM * BK) + (r % BM) * BK + c % BK;
-}
 // Element (r, c) of the low plane: the plane is an array of BM x BN tiles in row-major tile order.
 __device__ __forceinline__ int64_t split_lo_index(int64_t r, int64_t c, int64_t tiles_n)
 {
@@ -646,7 +636,7 @@ __global__ __launch_bounds__(256) void split_from_w_kernel(const float* __restri
             l = u32x4{split_lo(a0) | (split_lo(a1) << 16), split_lo(a2) | (split_lo(a3) << 16),
                       split_lo(b0) | (split_lo(b1) << 16), split_lo(b2) | (split_lo(b3) << 16)};
         }
-        *reinterpret_cast<u32x4*>(hi + split_hi_index(r, c, pitch)) = h;
+        *reinterpret_cast<u32x4*>(hi + operand_index(r, c, pitch)) = h;
         if (c < cols) *reinterpret_cast<u32x4*>(lo + split_lo_index(r, c, tiles_n)) = l;
     }
 }
@@ -658,7 +648,7 @@ __global__ __launch_bounds__(256) void w_from_split_kernel(const uint16_t* __res
     const int64_t chunks = cols / 8, total = rows * chunks;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
         const int64_t r = idx / chunks, c = (idx % chunks) * 8;
-        const u32x4 h = *reinterpret_cast<const u32x4*>(hi + split_hi_index(r, c, pitch));
+        const u32x4 h = *reinterpret_cast<const u32x4*>(hi + operand_index(r, c, pitch));
         const u32x4 l = *reinterpret_cast<const u32x4*>(lo + split_lo_index(r, c, tiles_n));
         const uint32_t h0 = h[0], h1 = h[1], h2 = h[2], h3 = h[3], l0 = l[0], l1 = l[1], l2 = l[2], l3 = l[3];
         const floatx4 a = {split_join(h0 & 0xffffu, l0 & 0xffffu), split_join(h0 >> 16, l0 >> 16),
@@ -733,7 +723,7 @@ hipError_t launch_shadow_from_w(const float* W, uint16_t* shadow, int64_t J, int
 }
 
 hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, float* Z, uint16_t* X_aligned,
-                                   int64_t B, int64_t J, int64_t D, hipStream_t stream, bool w_blocked)
+                                   int64_t B, int64_t J, int64_t D, hipStream_t stream)
 {
     if (B <= 0 || J <= 0) return hipSuccess;
     const int64_t pitch = bf16_pitch(D);
@@ -746,7 +736,6 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
     Params p = {};
     p.A = X_aligned; p.lda = pitch; p.M = B;
     p.B = W_shadow; p.ldb = pitch; p.N = J;
-    p.b_blocked = w_blocked ? 1 : 0;
     p.C = Z; p.ldc = J;
     p.c_blocked = 1;             // logits tile by tile: a workgroup writes 256 KB in one piece (see mlr_logits_floats)
     p.K = pitch;
@@ -758,20 +747,17 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
 // Floats of the tile-blocked logits array of launch_mlr_forward_bf16.
 int64_t mlr_logits_floats(int64_t B, int64_t J) { return ((B + BM - 1) / BM) * ((J + BN - 1) / BN) * (int64_t)(BM * BN); }
 
-// Bytes of the high plane of a J x D matrix kept as two planes (whole blocks of 256 rows).
-int64_t split_hi_bytes(int64_t J, int64_t D) { return ((J + BM - 1) / BM) * (int64_t)BM * bf16_pitch(D) * 2; }
+// Bytes of a rows x cols bf16 operand in the blocked layout (whole blocks of 256 rows, cols padded to 64).
+int64_t bf16_operand_bytes(int64_t rows, int64_t cols) { return ((rows + BM - 1) / BM) * (int64_t)BM * bf16_pitch(cols) * 2; }
 // Bytes of the low plane of a J x D matrix kept as two planes (whole 256 x 256 tiles).
 int64_t split_lo_bytes(int64_t J, int64_t D) { return ((J + BM - 1) / BM) * ((D + BN - 1) / BN) * (int64_t)(BM * BN) * 2; }
 
-// U^T and V^T in blocks of 256 rows x 64 columns: whole row blocks.
-int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D)
-{
-    return ((J + BM - 1) / BM * BM + (D + BN - 1) / BN * BN) * bf16_pitch(N) * 2;
-}
+// U^T (J x N) and V^T (D x N) in the operand layout, one after the other.
+int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D) { return bf16_operand_bytes(J, N) + bf16_operand_bytes(D, N); }
 
 uint16_t* apply_bf16_vt(void* workspace, int64_t N, int64_t J)
 {
-    return static_cast<uint16_t*>(workspace) + (J + BM - 1) / BM * BM * bf16_pitch(N);
+    return static_cast<uint16_t*>(workspace) + bf16_operand_bytes(J, N) / 2;
 }
 
 hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, const float* coef, int64_t N, int64_t J,
@@ -815,7 +801,6 @@ hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64
     Params p = {};
     p.A = Ut; p.lda = Np; p.M = J;
     p.B = Vt; p.ldb = Np; p.N = D;
-    p.a_blocked = p.b_blocked = 1;
     p.C = W; p.ldc = D;
     p.shadow = W_shadow; p.ld_shadow = bf16_pitch(D);
     p.K = Np;

@@ -44,20 +44,21 @@ int64_t gemm_f32_partial_bytes(int64_t M, int64_t N, int64_t K);
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel of the large MLR path (fp32 accumulate) and its layout helpers.
 // ---------------------------------------------------------------------------
-// Row pitch (elements) of the aligned bf16 operands: cols rounded up to 64.
+// Every bf16 operand of the kernel (the aligned copy of X, the working copy / high plane of W, U^T, V^T) is
+// stored in blocks of 256 rows x 64 columns, columns zero-padded to bf16_pitch(cols): element (r, c) of a
+// rows x cols operand sits at ((r / 256) * (pitch / 64) + c / 64) * 16384 + (r % 256) * 64 + c % 64, so that a
+// k-slice of a 256-row tile is one 32 KB piece.  bf16_operand_bytes: size of such an array (whole row blocks).
 int64_t bf16_pitch(int64_t cols);
-// shadow[j][0..pitch) = bf16(W[j][0..D)), zero padded; pitch = bf16_pitch(D).
+int64_t bf16_operand_bytes(int64_t rows, int64_t cols);
+// shadow = bf16(W) (round to nearest even), J x D, in that layout.
 hipError_t launch_shadow_from_w(const float* W, uint16_t* shadow, int64_t J, int64_t D, hipStream_t stream);
-// z(b, j) = sum_d X[b][d] * shadow[j][d];  X bf16 [B][D].  The logits are stored tile by tile:
+// z(b, j) = sum_d X[b][d] * shadow(j, d);  X bf16 [B][D] row-major, or null if X_aligned (B x D in the operand
+// layout, bf16_operand_bytes(B, D)) has already been filled.  The logits are stored tile by tile:
 // Z is an array of 256 x 256 tiles (mlr_logits_floats(B, J) floats), tile (b / 256, j / 256) at index
-// (j / 256) * ceil(B / 256) + b / 256, rows of 256 floats inside a tile; launch_mlr_softmax(..., blocked_rows = B)
+// (j / 256) * ceil(B / 256) + b / 256, rows of 256 floats inside a tile; launch_mlr_softmax(..., blocked = true)
 // reads that layout.
-// X_aligned: scratch for the aligned copy of X, B * bf16_pitch(D) elements.
-// X == nullptr: X_aligned already holds the samples (rows zero padded to the pitch).
-// w_blocked: W_shadow is the high plane of a matrix kept as two planes (launch_split_from_w) instead of a
-// row-major working copy.
 hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, float* Z, uint16_t* X_aligned,
-                                   int64_t B, int64_t J, int64_t D, hipStream_t stream, bool w_blocked = false);
+                                   int64_t B, int64_t J, int64_t D, hipStream_t stream);
 // W[j][d] -= eta * sum_i U[i][j] * V[i][d];  U bf16 [N][J], V bf16 [N][D], W fp32 [J][D].
 // Two steps: launch_apply_bf16_transpose writes U^T and V^T into `workspace`
 // (apply_bf16_workspace_bytes, 256-byte aligned), launch_apply_bf16 consumes them.
@@ -65,9 +66,8 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
 int64_t mlr_logits_floats(int64_t B, int64_t J);
 int64_t apply_bf16_workspace_bytes(int64_t N, int64_t J, int64_t D);
 // coef (nullable, device, N floats): V^T is written as bf16(coef[i] * V[i][d]).
-// U^T and V^T are stored in blocks of 256 rows x 64 columns (block (r / 256, k / 64) at index
-// (r / 256) * (bf16_pitch(N) / 64) + k / 64).  V == nullptr: only U^T is written; the caller fills V^T in that
-// layout at apply_bf16_vt(workspace, N, J) (round_up(D, 256) * bf16_pitch(N) elements, columns N.. zero).
+// U^T (J x N) and V^T (D x N) are written into the workspace in the operand layout.  V == nullptr: only U^T is
+// written; the caller fills V^T at apply_bf16_vt(workspace, N, J) (bf16_operand_bytes(D, N), columns N.. zero).
 uint16_t* apply_bf16_vt(void* workspace, int64_t N, int64_t J);
 hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, const float* coef, int64_t N, int64_t J,
                                        int64_t D, void* workspace, hipStream_t stream);
@@ -75,11 +75,9 @@ hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, con
 // to bf16) and W_lo the low one; both are updated and the fp32 array W is not touched.
 hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64_t N, int64_t J, int64_t D, float eta,
                              const void* workspace, hipStream_t stream);
-// fp32 W[J][D] <-> planes hi (split_hi_bytes(J, D) bytes: blocks of 256 rows x 64 columns, the k-slices of the
-// forward contraction's row tiles, each 32 KB in one piece; columns D.. of the pitch are zero) and lo
-// (split_lo_bytes(J, D) bytes: 256 x 256 tiles in row-major tile order, one piece per workgroup of the apply):
+// fp32 W[J][D] <-> planes hi (a J x D bf16 operand, bf16_operand_bytes(J, D)) and lo (split_lo_bytes(J, D)
+// bytes: 256 x 256 tiles in row-major tile order, one piece per workgroup of the apply):
 // bits = (hi << 16) + sign_extend(lo).
-int64_t split_hi_bytes(int64_t J, int64_t D);
 int64_t split_lo_bytes(int64_t J, int64_t D);
 hipError_t launch_split_from_w(const float* W, uint16_t* hi, uint16_t* lo, int64_t J, int64_t D, hipStream_t stream);
 hipError_t launch_w_from_split(const uint16_t* hi, const uint16_t* lo, float* W, int64_t J, int64_t D, hipStream_t stream);
@@ -90,8 +88,8 @@ void set_bf16_variant(int forward_variant, int apply_variant);
 // CSR rows (indptr int64 [rows + 1], indices int32, values fp32 or bf16).
 // ---------------------------------------------------------------------------
 // dst[r * row_stride + c * col_stride] = value (* coef[r] if coef) for every stored
-// entry (r, c); dst must have been zero-filled.  col_stride = -P (P % 64 == 0) instead writes the transpose
-// [cols][P] in the blocked operand layout of the bf16 contractions (blocks of 256 rows x 64 columns).  Entries outside [0, cols) and row
+// entry (r, c); dst must have been zero-filled.  In the operand layout of the bf16 contractions instead:
+// row_stride = -P writes the rows x cols matrix itself (pitch P), col_stride = -P its transpose (cols x rows, pitch P).  Entries outside [0, cols) and row
 // ranges outside [0, nnz] are skipped.
 hipError_t launch_csr_scatter(const int64_t* indptr, const int32_t* indices, const void* values, bool bf16,
                               const float* coef, void* dst, int64_t rows, int64_t cols, int64_t nnz,

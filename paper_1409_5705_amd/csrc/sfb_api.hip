@@ -250,7 +250,7 @@ int64_t sfb_workspace_bytes(int32_t model, int64_t J, int64_t D, const sfb_batch
     switch (model) {
         case SFB_MLR:
             if (batch->in_dtype == SFB_BF16)   // logits (tile-blocked), aligned copy of X, bf16 copy of W
-                return round_up(sfb::mlr_logits_floats(B, J) * 4) + round_up(B * sfb::bf16_pitch(D) * 2) + sfb_shadow_bytes(J, D);
+                return round_up(sfb::mlr_logits_floats(B, J) * 4) + round_up(sfb::bf16_operand_bytes(B, D)) + sfb_shadow_bytes(J, D);
             return round_up(B * J * 4) + round_up(sfb::gemm_f32_partial_bytes(B, J, D));   // logits, k-split scratch
         case SFB_DML:
             return round_up(B * J * 4) + round_up(sfb::gemm_f32_partial_bytes(B, J, D));   // projections Q[B][K], k-split scratch
@@ -262,7 +262,7 @@ int64_t sfb_workspace_bytes(int32_t model, int64_t J, int64_t D, const sfb_batch
 int64_t sfb_shadow_bytes(int64_t J, int64_t D)
 {
     if (J <= 0 || D <= 0 || D % 8 != 0) return SFB_EINVAL;
-    return round_up(J * sfb::bf16_pitch(D) * 2);
+    return round_up(sfb::bf16_operand_bytes(J, D));
 }
 
 int sfb_shadow_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* dev_ptr, int64_t bytes)
@@ -294,7 +294,7 @@ int sfb_shadow_detach(sfb_ctx* ctx)
 int64_t sfb_split_bytes(int64_t J, int64_t D)
 {
     const int64_t plane = sfb_shadow_bytes(J, D);
-    return plane < 0 ? plane : round_up(sfb::split_hi_bytes(J, D)) + round_up(sfb::split_lo_bytes(J, D));
+    return plane < 0 ? plane : round_up(sfb::bf16_operand_bytes(J, D)) + round_up(sfb::split_lo_bytes(J, D));
 }
 
 int sfb_split_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* dev_ptr, int64_t bytes)
@@ -308,7 +308,7 @@ int sfb_split_attach(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, void* d
     if (reinterpret_cast<uintptr_t>(dev_ptr) % ALIGN != 0) return SFB_EINVAL;
     SFB_TRY(hipSetDevice(ctx->device));
     uint16_t* hi = static_cast<uint16_t*>(dev_ptr);
-    uint16_t* lo = hi + round_up(sfb::split_hi_bytes(J, D)) / 2;
+    uint16_t* lo = hi + round_up(sfb::bf16_operand_bytes(J, D)) / 2;
     SFB_RUN(KID_SHADOW, sfb::launch_split_from_w(W, hi, lo, J, D, ctx->stream));
     ctx->shadow_W = W;
     ctx->shadow_buf = hi;
@@ -391,13 +391,12 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
             uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + round_up(sfb::mlr_logits_floats(B, J) * 4));
             const uint16_t* Wb = ctx->shadow_buf;
             if (!has_shadow) {   // no working copy attached: make one for this call
-                uint16_t* tmp = Xa + round_up(B * sfb::bf16_pitch(D) * 2) / 2;
+                uint16_t* tmp = Xa + round_up(sfb::bf16_operand_bytes(B, D)) / 2;
                 SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, tmp, J, D, st));
                 Wb = tmp;
             }
             SFB_RUN(KID_FORWARD_BF16,
-                    sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), Wb, Z, Xa, B, J, D, st,
-                                                 is_split(ctx, W)));
+                    sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), Wb, Z, Xa, B, J, D, st));
             SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true));
         }
         if (V && V != batch->X)
@@ -621,13 +620,13 @@ int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb
     uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + round_up(sfb::mlr_logits_floats(B, J) * 4));
     const uint16_t* Wb = ctx->shadow_buf;
     if (!has_shadow) {
-        uint16_t* tmp = Xa + round_up(B * pitch * 2) / 2;
+        uint16_t* tmp = Xa + round_up(sfb::bf16_operand_bytes(B, D)) / 2;
         SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, tmp, J, D, st));
         Wb = tmp;
     }
-    SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xa, 0u, B * pitch / 2, st));
-    SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, true, nullptr, Xa, B, D, X->nnz, pitch, 1, st));
-    SFB_RUN(KID_FORWARD_BF16, sfb::launch_mlr_forward_bf16(nullptr, Wb, Z, Xa, B, J, D, st, is_split(ctx, W)));
+    SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xa, 0u, sfb::bf16_operand_bytes(B, D) / 4, st));
+    SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, true, nullptr, Xa, B, D, X->nnz, -pitch, 1, st));
+    SFB_RUN(KID_FORWARD_BF16, sfb::launch_mlr_forward_bf16(nullptr, Wb, Z, Xa, B, J, D, st));
     SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true));
     return SFB_OK;
 }
@@ -676,7 +675,7 @@ int sfb_apply_csr(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, c
     }
     const int64_t Np = sfb::bf16_pitch(N);
     uint16_t* Vt = sfb::apply_bf16_vt(ctx->ws, N, J);
-    SFB_RUN(KID_FILL, sfb::launch_fill_u32(Vt, 0u, (D + 255) / 256 * 256 * Np / 2, st));
+    SFB_RUN(KID_FILL, sfb::launch_fill_u32(Vt, 0u, sfb::bf16_operand_bytes(D, N) / 4, st));
     SFB_RUN(KID_CSR, sfb::launch_csr_scatter(V->indptr, V->indices, V->values, true, coef, Vt, N, D, V->nnz, 1, -Np, st));
     SFB_RUN(KID_APPLY_TRANSPOSE, sfb::launch_apply_bf16_transpose(static_cast<const uint16_t*>(U), nullptr, nullptr, N, J,
                                                                   D, ctx->ws, st));

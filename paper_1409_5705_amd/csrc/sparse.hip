@@ -50,9 +50,11 @@ __global__ __launch_bounds__(256) void csr_scatter_kernel(const int64_t* __restr
                 else
                     v = c * v;
             }
-            // col_stride < 0: transposed into blocks of 256 rows x 64 columns, -col_stride = columns of the transpose
-            const int64_t at = col_stride < 0 ? ((col / 256) * (-col_stride / 64) + r / 64) * 16384 + (col % 256) * 64 + r % 64
-                                              : r * row_stride + col * col_stride;
+            // negative strides: blocks of 256 rows x 64 columns (the operand layout of the bf16 contractions);
+            // col_stride = -pitch: the transpose, row_stride = -pitch: the matrix itself
+            const int64_t at = col_stride < 0   ? ((col / 256) * (-col_stride / 64) + r / 64) * 16384 + (col % 256) * 64 + r % 64
+                               : row_stride < 0 ? ((r / 256) * (-row_stride / 64) + col / 64) * 16384 + (r % 256) * 64 + col % 64
+                                                : r * row_stride + col * col_stride;
             dst[at] = v;
         }
     }
