@@ -367,6 +367,23 @@ def main():
     if split:
         ctx.sfb_split_export(W)      # (outside the timed region: the fp32 array is only a snapshot in this layout)
         torch.cuda.synchronize()
+    # The apply rewrites the bf16 image of W (high plane / working copy) four columns at a time and only where
+    # its bits change.  Share of such groups in one more, untimed step, on a sample of rows: it sets the bytes
+    # that step has to write.
+    rows = slice(0, min(J, 4096))
+
+    def bf16_image(Wrows):
+        bits = Wrows.contiguous().view(torch.int32).to(torch.int64)
+        return ((bits + 0x8000) >> 16) if split else Wrows.bfloat16().view(torch.int16).to(torch.int64)
+
+    image_before = bf16_image(W[rows])
+    step(args.warmup + args.steps)
+    if split:
+        ctx.sfb_split_export(W)
+    torch.cuda.synchronize()
+    rewritten = float((bf16_image(W[rows]) != image_before).view(-1, D // 4, 4).any(dim=2).float().mean()) \
+        if not args.no_shadow else 0.0
+    del image_before
     assert bool(torch.isfinite(W[:1024]).all())
 
     # per-kernel averages from the HIP events recorded on the library's stream
@@ -381,8 +398,10 @@ def main():
     # algorithmic HBM bytes per launch (the bf16 working copy of W counts: read by forward, written by apply)
     wb = 2 if not args.no_shadow else 4
     fwd_bytes = J * D * wb + B * D * 2 + B * J * 4           # W (copy / high plane) read once, X, logits written
-    app_bytes = 2 * J * D * 4 + (J * D * 2 if (not args.no_shadow and not split) else 0) + B * J * 2 + B * D * 2
-    # ^ W read + written once (4 bytes per element each way in either layout), bf16 copy written (fp32 layout), U^T, V^T read
+    if split:      # both planes read, low plane written, high plane written where it changes, U^T, V^T read
+        app_bytes = J * D * (4 + 2 + 2 * rewritten) + B * J * 2 + B * D * 2
+    else:          # W read and written, bf16 copy written where it changes, U^T, V^T read
+        app_bytes = J * D * (8 + (2 * rewritten if not args.no_shadow else 0)) + B * J * 2 + B * D * 2
     tr_bytes = 2 * (B * J * 2 + B * D * 2)                   # U, V read; U^T, V^T written
     smx_bytes = B * J * 4 + B * J * 2                        # logits read once, U written
     stages = {
@@ -400,7 +419,9 @@ def main():
                        "hbm_gbs": app_bytes / app_ms / 1e6, "hbm_frac": app_bytes / app_ms / 1e6 / PEAK_HBM_GBS},
     }
     # Roofline of the dominant kernel.  At this shape the forward contraction is
-    # MFMA-bound (845 flop/B) and the apply is HBM-bound (200 flop/B < ridge 312).
+    # MFMA-bound (845 flop/B); the apply is bound by whichever roof its flops per
+    # algorithmic byte put it under (ridge: 312 flop/B; 250 with the fp32 array,
+    # 330 with the two planes when hardly any high half changes).
     # `traffic`: HBM-side bytes per launch of that kernel from the rocprofv3 --pmc
     # passes (FETCH_SIZE, WRITE_SIZE, scaled by the copy-kernel calibration) that
     # the committed summary under profiles/ records; null if it has no such line.
@@ -410,9 +431,17 @@ def main():
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": stages["forward_gemm"]["mfma_frac"],
                 "traffic": traffic.get("sf_gemm_kernel<0>")}
     else:
-        roof = {"kernel": ("sf_gemm_kernel<2> (apply on the two planes)" if split else "sf_gemm_kernel<1> (apply)"), "bound": "hbm", "achieved": stages["apply_gemm"]["hbm_gbs"],
-                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": stages["apply_gemm"]["hbm_frac"],
-                "traffic": traffic.get("sf_gemm_kernel<2>" if split else "sf_gemm_kernel<1>")}
+        name = "sf_gemm_kernel<2> (apply on the two planes)" if split else "sf_gemm_kernel<1> (apply)"
+        if gemm_flops / app_bytes > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+            roof = {"kernel": name, "bound": "mfma", "achieved": stages["apply_gemm"]["tflops"],
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": stages["apply_gemm"]["mfma_frac"]}
+        else:
+            roof = {"kernel": name, "bound": "hbm", "achieved": stages["apply_gemm"]["hbm_gbs"],
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": stages["apply_gemm"]["hbm_frac"]}
+        roof["traffic"] = traffic.get("sf_gemm_kernel<2>" if split else "sf_gemm_kernel<1>")
+        roof["flop_per_algorithmic_byte"] = gemm_flops / app_bytes
+        roof["algorithmic_bytes"] = app_bytes
+        roof["bf16_image_groups_rewritten"] = rewritten
     roof["traffic_unit"] = "bytes per launch (rocprofv3 --pmc, separate run; see profiles/)"
 
     out = {

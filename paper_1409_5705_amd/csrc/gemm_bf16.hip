@@ -407,7 +407,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                         const float n3f = split_join(hB >> 16, lB >> 16) - p.eta * v3;
                         const u32x2 oh = {split_hi(n0f) | (split_hi(n1f) << 16), split_hi(n2f) | (split_hi(n3f) << 16)};
                         const u32x2 ol = {split_lo(n0f) | (split_lo(n1f) << 16), split_lo(n2f) | (split_lo(n3f) << 16)};
-                        __builtin_amdgcn_raw_buffer_store_b64(oh, srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
+                        // the high halves change only where the update crosses a bf16 rounding boundary: lanes
+                        // whose four are unchanged leave the plane as it is (the same bits, fewer bytes written)
+                        if (oh[0] != hA || oh[1] != hB)
+                            __builtin_amdgcn_raw_buffer_store_b64(oh, srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
                         __builtin_amdgcn_raw_buffer_store_b64(ol, lrs, lane_l, (uint32_t)dr * row_l, C_POLICY);
                     } else {
                         const uint32_t o0 = w[q % EPD][e][0], o1 = w[q % EPD][e][1], o2 = w[q % EPD][e][2],
@@ -417,9 +420,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                         const u32x4 out = {__float_as_uint(n0f), __float_as_uint(n1f), __float_as_uint(n2f),
                                            __float_as_uint(n3f)};
                         __builtin_amdgcn_raw_buffer_store_b128(out, crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
-                        if (has_shadow) {
+                        if (has_shadow) {   // the copy is current on entry: rewrite it only where its bits change
                             const u32x2 sh = {pack_bf16(n0f, n1f), pack_bf16(n2f, n3f)};
-                            __builtin_amdgcn_raw_buffer_store_b64(sh, srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
+                            if (sh[0] != pack_bf16(__uint_as_float(o0), __uint_as_float(o1)) ||
+                                sh[1] != pack_bf16(__uint_as_float(o2), __uint_as_float(o3)))
+                                __builtin_amdgcn_raw_buffer_store_b64(sh, srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
                         }
                     }
                 }

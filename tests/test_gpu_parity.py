@@ -225,8 +225,14 @@ def test_bf16_shadow_stays_current(sfb, oracle):
         if step == 2:
             Uo, _ = oracle.mlr_sf(host(Wb), X, y)
             assert rel_err(host(Ua), Uo) <= TOL_BF16
-        ca.sfb_apply(Wa, Ua, Xd, eta); cb.sfb_apply(Wb, Ub, Xd, eta)
+        before = Wb.bfloat16()
+        step_eta = eta if step != 1 else eta * 1e-4          # the small one leaves most bf16 values as they are
+        ca.sfb_apply(Wa, Ua, Xd, step_eta); cb.sfb_apply(Wb, Ub, Xd, step_eta)
         assert torch.equal(Wa, Wb)
+        # the copy is rewritten four columns at a time, and only where its bits change: both cases must occur
+        moved = (Wb.bfloat16() != before).view(J, D // 4, 4).any(dim=2).float().mean().item()
+        print("  groups of four whose bf16 value changed: %.3f" % moved, flush=True)
+        assert moved > 0.0 and (step != 1 or moved < 0.9)
         if step == 1:
             ca.sfb_prox_rows(Wa, sfb.SFB_PROX_PROJECT); cb.sfb_prox_rows(Wb, sfb.SFB_PROX_PROJECT)
     # a caller-side change of W must be followed by a refresh
