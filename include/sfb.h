@@ -88,7 +88,9 @@ int64_t sfb_apply_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dt
  * library never frees it) and remembers (W, J, D).  While attached,
  *   - sfb_compute_sf(SFB_MLR, bf16) on that W reads the copy and needs
  *     sfb_shadow_bytes less workspace;
- *   - sfb_apply and sfb_prox_rows on that W keep the copy current;
+ *   - sfb_apply and sfb_prox_rows on that W keep the copy current (sfb_apply
+ *     relies on it being current on entry: it rewrites only the entries whose
+ *     bf16 value changes);
  *   - any other modification of W by the caller must be followed by another
  *     sfb_shadow_attach (a refresh), otherwise the copy is stale.
  * Without an attached copy the bf16 path converts W into the workspace on every
@@ -108,10 +110,10 @@ int sfb_shadow_detach(sfb_ctx* ctx);
  * blocks of 256 rows x 64 columns, lo in tiles of 256 x 256, each block one
  * contiguous piece); the layout is the library's business, the caller only provides
  * sfb_split_bytes bytes.  The forward contraction reads the hi plane as its bf16
- * operand; sfb_apply reads and writes both planes, i.e. the same 8 bytes per
- * element as a read-modify-write of the fp32 array, with the same fp32 arithmetic
- * and the same resulting bits, but without the third write that keeps a separate
- * working copy current.
+ * operand; sfb_apply reads both planes and writes the lo plane, and the hi plane
+ * only where the update moves a value across a bf16 rounding boundary (6 to 8 bytes
+ * per element against 8 to 10 for the fp32 array plus working copy), with the same
+ * fp32 arithmetic and the same resulting bits.
  * sfb_split_attach converts W into the caller-allocated buffer (sfb_split_bytes,
  * 256-byte aligned; never freed by the library) and remembers (W, J, D).  While
  * attached, the planes ARE the parameters and the fp32 array W is a stale
