@@ -268,8 +268,6 @@ def main():
                          "and report what this GPU sustains next to the published peaks")
     ap.add_argument("--csr", action="store_true",
                     help="mlr_large_bf16: hand the samples over as CSR rows (sfb_mlr_sf_csr / sfb_apply_csr)")
-    ap.add_argument("--forward-variant", type=int, default=-1)
-    ap.add_argument("--apply-variant", type=int, default=-1)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (each GPU box has one GPU); "
@@ -306,7 +304,6 @@ def main():
     J, D, B, eta = cfg["J"], cfg["D"], cfg["B"], cfg["eta"]
     dev = torch.device("cuda", 0)
     sfb.lib()
-    sfb.sfb_tune_bf16_variant(args.forward_variant, args.apply_variant)
 
     log("bench: generating inputs (W %.1f GB on device)" % (J * D * 4 / 1e9))
     gen = torch.Generator(device=dev)

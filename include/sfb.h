@@ -302,11 +302,18 @@ typedef struct {
 int sfb_profile_enable(sfb_ctx* ctx, int on);
 int sfb_profile_collect(sfb_ctx* ctx, sfb_kernel_time* out, int max_entries, int* count);
 
-/* Timing-experiment knob of the bf16 forward / apply kernel (process-wide;
- * -1 or 0 = normal operation).  value / 100 is a bit set: 2 = skip the
- * epilogue (nothing is written), 8 = do not refresh the bf16 working copy.
- * Results are only valid at 0. */
-void sfb_tune_bf16_variant(int forward_variant, int apply_variant);
+/*
+ * Bound of the only in-kernel wait of the library (process-wide).  For rows of
+ * 65536 classes or more the softmax of the bf16 multiclass-logistic path is
+ * computed by several workgroups per row, each keeping its part of the row in
+ * registers so that the logits are read once; they exchange one (max, sum) pair
+ * per row through the workspace.  A workgroup polls a partner's pair at most
+ * `polls` times (about a microsecond each; default 1000, restored by a negative
+ * argument) and then computes that pair itself from the logits, so the result
+ * never depends on which workgroups are on the chip together; 0 makes every
+ * workgroup do so at once (same results; meant for tests of that path).
+ */
+void sfb_set_wait_limit(int polls);
 
 #ifdef __cplusplus
 }

@@ -132,8 +132,8 @@ def lib():
         L.sfb_profile_collect.argtypes = [vp, ctypes.POINTER(sfb_kernel_time), ctypes.c_int,
                                           ctypes.POINTER(ctypes.c_int)]
         L.sfb_profile_collect.restype = ctypes.c_int
-        L.sfb_tune_bf16_variant.argtypes = [ctypes.c_int, ctypes.c_int]
-        L.sfb_tune_bf16_variant.restype = None
+        L.sfb_set_wait_limit.argtypes = [ctypes.c_int]
+        L.sfb_set_wait_limit.restype = None
         L.sfb_ssp_create.argtypes = [ctypes.POINTER(vp), i32, i32]
         L.sfb_ssp_create.restype = ctypes.c_int
         L.sfb_ssp_destroy.argtypes = [vp]
@@ -166,8 +166,8 @@ def version() -> str:
     return lib().sfb_version().decode()
 
 
-def sfb_tune_bf16_variant(forward_variant: int = -1, apply_variant: int = -1) -> None:
-    lib().sfb_tune_bf16_variant(int(forward_variant), int(apply_variant))
+def sfb_set_wait_limit(polls: int = -1) -> None:
+    lib().sfb_set_wait_limit(int(polls))
 
 
 def _dtype_code(t: torch.Tensor) -> int:

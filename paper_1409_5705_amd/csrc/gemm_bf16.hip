@@ -103,7 +103,6 @@ struct Params {
     int tiles_m, tiles_n;
     int64_t tiles_total;
     int group_m;        // raster: groups of group_m row-tiles, row-tile index fastest inside a group
-    int dbg;            // timing experiments: 2 = skip epilogue, 8 = no shadow store
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
@@ -342,7 +341,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                                    : (MODE == MODE_FWD && p.c_blocked)
                                        ? p.C + ((n0 / BN) * p.tiles_m + m0 / BM) * (int64_t)(BM * BN) + wm0 * BN + wn0
                                        : p.C + (m0 + wm0) * p.ldc + n0 + wn0);
-        const bool has_shadow = p.shadow && !(p.dbg & 8);
+        const bool has_shadow = p.shadow != nullptr;
         // (the bf16 copy / high plane is stored in the operand layout: blocks of BM rows x 64 columns)
         const auto srs = make_rsrc((MODE == MODE_SPLIT || has_shadow)
                                        ? p.shadow + ((m0 / BM) * (p.ld_shadow / BK) + (n0 + wn0) / BK) * (int64_t)(BM * BK) + wm0 * BK
@@ -534,12 +533,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
         tile_origin(t, m0, n0);
         slice_body(std::true_type{});
         for (int64_t k = 1; k < nk; ++k) slice_body(std::false_type{});
-        if (!(p.dbg & 2)) {
-            if ((m0 + BM <= p.M) && (n0 + BN <= p.N))
-                epilogue_tile(m0, n0, std::false_type{});
-            else
-                epilogue_tile(m0, n0, std::true_type{});
-        }
+        if ((m0 + BM <= p.M) && (n0 + BN <= p.N))
+            epilogue_tile(m0, n0, std::false_type{});
+        else
+            epilogue_tile(m0, n0, std::true_type{});
     }
     wait_all_vmem();   // no direct load may be in flight when the workgroup's LDS is released
 }
@@ -665,9 +662,6 @@ __global__ __launch_bounds__(256) void w_from_split_kernel(const uint16_t* __res
     }
 }
 
-int g_forward_dbg = 0;   // timing experiments only: 2 = no epilogue, 8 = no shadow store
-int g_apply_dbg = 0;
-
 template <int MODE>
 hipError_t launch(Params p, hipStream_t stream)
 {
@@ -710,12 +704,6 @@ unsigned grid_for(int64_t n)
 
 }  // namespace
 
-void set_bf16_variant(int forward_variant, int apply_variant)
-{
-    g_forward_dbg = forward_variant < 0 ? 0 : forward_variant / 100;
-    g_apply_dbg = apply_variant < 0 ? 0 : apply_variant / 100;
-}
-
 int64_t bf16_pitch(int64_t cols) { return (cols + BK - 1) / BK * BK; }
 
 hipError_t launch_shadow_from_w(const float* W, uint16_t* shadow, int64_t J, int64_t D, hipStream_t stream)
@@ -745,7 +733,6 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
     p.c_blocked = 1;             // logits tile by tile: a workgroup writes 256 KB in one piece (see mlr_logits_floats)
     p.K = pitch;
     p.group_m = 0;               // all batch tiles of one class tile are neighbours (they share the W tile)
-    p.dbg = g_forward_dbg;
     return launch<MODE_FWD>(p, stream);
 }
 
@@ -811,7 +798,6 @@ hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64
     p.K = Np;
     p.eta = eta;
     p.group_m = 8;               // 8 row-tiles x 4 column tiles under one L2 at a time (measured best of 1..32)
-    p.dbg = g_apply_dbg;
     if (W_lo) {
         p.lo = W_lo;
         return launch<MODE_SPLIT>(p, stream);

@@ -81,8 +81,6 @@ hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64
 int64_t split_lo_bytes(int64_t J, int64_t D);
 hipError_t launch_split_from_w(const float* W, uint16_t* hi, uint16_t* lo, int64_t J, int64_t D, hipStream_t stream);
 hipError_t launch_w_from_split(const uint16_t* hi, const uint16_t* lo, float* W, int64_t J, int64_t D, hipStream_t stream);
-// Timing experiments (benchmark sweeps): variant / 100 = debug bits; -1 = normal.
-void set_bf16_variant(int forward_variant, int apply_variant);
 
 // ---------------------------------------------------------------------------
 // CSR rows (indptr int64 [rows + 1], indices int32, values fp32 or bf16).
@@ -103,8 +101,13 @@ hipError_t launch_csr_check(const int64_t* indptr, const int32_t* indices, int64
 // ---------------------------------------------------------------------------
 // U[i][j] = exp(Z[i][j] - max_i) / sum_i - [j == y[i]];  out_bf16 selects the U dtype.
 // blocked: Z is the tile-blocked array written by launch_mlr_forward_bf16 instead of a row-major [B][J].
-hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool out_bf16,
-                              int64_t B, int64_t J, hipStream_t stream, bool blocked = false);
+// scratch: mlr_softmax_scratch_bytes(B, J) bytes (8-byte aligned; contents irrelevant) or null; with it, blocked
+// logits of long rows are read once, by several workgroups per row that exchange their partial sums through it.
+int64_t mlr_softmax_scratch_bytes(int64_t B, int64_t J);
+// Polls of a partner's word before a workgroup of that kernel does the partner's part itself (< 0: default).
+void set_softmax_spin_limit(int polls);
+hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool out_bf16, int64_t B, int64_t J,
+                              hipStream_t stream, bool blocked = false, void* scratch = nullptr);
 // V = X - Y (elementwise, n elements).
 hipError_t launch_diff(const float* X, const float* Y, float* V, int64_t n, hipStream_t stream);
 // DML coefficient: d = ||Q_i||^2; c = +2 (sim>0), -2 (sim<=0 and d<margin), else 0; U_i = c Q_i.

@@ -11,6 +11,8 @@ namespace {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float wave_sum(float v)
 {
@@ -147,6 +149,173 @@ __global__ __launch_bounds__(NT) void mlr_softmax_kernel(const float* __restrict
         } else {
             reinterpret_cast<float*>(Uv)[row * J + j] = p;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The same for long rows of tile-blocked logits, reading them once.  A row of
+// the headline size (1.3 MB) outlives every cache between the two passes above,
+// so the second pass is a second trip to memory.  Here CL workgroups share a
+// row: each keeps its 1/CL of the row in registers (up to CHUNKS x 16 bytes a
+// thread), reduces it to (max, sum of exponentials relative to that max),
+// publishes the pair in one 64-bit word and collects the CL words of the row;
+// the stored values become exp(z - max_own) and are rescaled on output.
+//
+// The grid is one workgroup per CU (1024 threads at no more than 128 registers), so
+// the CL partners of a row normally run at the same time, and they execute the
+// same number of row iterations.  Nothing depends on that, though: the wait for a
+// partner's word is bounded (spin_limit polls), and a workgroup whose partner has
+// not published in time (kernels of other streams can keep it off the chip)
+// computes that partner's pair itself from the logits, and no longer waits for that
+// partner in later rows.  So every workgroup finishes whatever the others do; the
+// price of a missing partner is reading its part of the row a second time.
+// `slots`: [B][CL] 64-bit words, all zero before the launch (a published word
+// has a non-zero high half: the bits of a sum that is at least 1).
+// ---------------------------------------------------------------------------
+constexpr int CLUSTER_CHUNKS = 10;        // 16-byte chunks of a row per thread
+
+__global__ __launch_bounds__(1024) void mlr_softmax_cluster_kernel(const float* __restrict__ Z,
+                                                                  const int32_t* __restrict__ y,
+                                                                  uint16_t* __restrict__ U, int64_t B, int64_t J,
+                                                                  int64_t tiles_m, int CL, int tiles_per_wg,
+                                                                  unsigned long long* __restrict__ slots, int spin_limit)
+{
+    constexpr int NT = 1024, R = CLUSTER_CHUNKS;
+    __shared__ float sm[NT / 64];
+    __shared__ float part_m[32], part_s[32];
+    __shared__ int part_ok[32], gone[32];       // gone: partners this workgroup has stopped waiting for
+    if (threadIdx.x < 32) gone[threadIdx.x] = 0;
+    const int tid = threadIdx.x;
+    const int groups = (int)gridDim.x / CL, grp = (int)blockIdx.x / CL, w = (int)blockIdx.x % CL;
+    if (grp >= groups) return;                      // (a grid that is not a multiple of CL: the rest has no row)
+    const int64_t tn = (J + 255) / 256;
+    const int64_t t0 = (int64_t)w * tiles_per_wg;
+    int64_t t1 = t0 + tiles_per_wg;
+    if (t1 > tn) t1 = tn;
+    const int64_t my_chunks = t1 > t0 ? (t1 - t0) * 64 : 0;      // 64 chunks of four classes per tile row
+
+    // Chunk i of this thread: tile t0 + 16 i + tid / 64, classes 4 (tid % 64) .. + 3 of it.  Addresses are a
+    // uniform part (row, i) plus a 32-bit part of the thread; which chunks exist does not depend on the row.
+    const uint32_t t_tile = (uint32_t)tid >> 6, t_col = ((uint32_t)tid & 63u) * 4u;
+    const uint32_t z_thread = t_tile * (uint32_t)(tiles_m * 65536) + t_col;        // floats; B <= 65536 (host check): < 2^28
+    const uint32_t j_thread = t_tile * 256u + t_col;
+    const int64_t z_step = 16 * tiles_m * 65536;                                   // floats from chunk i to i + 1
+    uint32_t have = 0;
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const int64_t c = (int64_t)i * NT + tid;
+        if (c < my_chunks && (t0 + (c >> 6)) * 256 + (c & 63) * 4 < J) have |= 1u << i;
+    }
+    // (buffer accesses: a uniform 64-bit base in scalar registers plus one 32-bit offset register per thread,
+    // instead of a 64-bit address pair per chunk)
+    auto rsrc = [](const void* base) {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0xffffffff, 0x00020000);
+    };
+    auto load_row = [&](int64_t row, floatx4* v) {
+        const float* base = Z + (row / 256) * 65536 + (row % 256) * 256 + t0 * tiles_m * 65536;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            v[i] = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            if (have & (1u << i)) {
+                const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rsrc(base + i * z_step), z_thread * 4u, 0, 0);
+                const uint32_t r0 = r[0], r1 = r[1], r2 = r[2], r3 = r[3];
+                v[i] = floatx4{__uint_as_float(r0), __uint_as_float(r1), __uint_as_float(r2), __uint_as_float(r3)};
+            }
+        }
+    };
+
+    floatx4 v[R], vn[R];
+    int64_t row = grp;
+    if (row < B) load_row(row, v);
+    for (; row < B; row += groups) {
+        // own part: maximum, then exponentials relative to it (kept in v) and their sum
+        float m = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < R; ++i) m = fmaxf(m, fmaxf(fmaxf(v[i][0], v[i][1]), fmaxf(v[i][2], v[i][3])));
+        const float m_own = block_max<NT>(m, sm);
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[i][e] = m_own == -INFINITY ? 0.f : expf(v[i][e] - m_own);
+                s += v[i][e];
+            }
+        }
+        float s_own = block_sum<NT>(s, sm);
+        if (m_own == -INFINITY) s_own = 1.0f;       // no class at all in this part: counts as 1 * exp(-inf) = 0
+        if (tid == 0) {
+            const unsigned long long word = ((unsigned long long)__float_as_uint(s_own) << 32) | __float_as_uint(m_own);
+            __hip_atomic_store(&slots[row * CL + w], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // the next row's loads travel while the partners' words are awaited and this row is written
+        const int64_t next = row + groups;
+        if (next < B) load_row(next, vn);
+        if (tid < CL) {
+            if (tid == w) {
+                part_m[tid] = m_own;
+                part_s[tid] = s_own;
+                part_ok[tid] = 1;
+            } else {
+                unsigned long long word = 0;
+                const int polls = gone[tid] ? 1 : spin_limit;
+                for (int spin = 0; spin < polls; ++spin) {
+                    word = __hip_atomic_load(&slots[row * CL + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (word >> 32) break;
+                    __builtin_amdgcn_s_sleep(8);
+                }
+                const int ok = (word >> 32) != 0;
+                part_m[tid] = __uint_as_float((uint32_t)word);
+                part_s[tid] = __uint_as_float((uint32_t)(word >> 32));
+                part_ok[tid] = ok;
+                if (!ok) gone[tid] = 1;
+            }
+        }
+        __syncthreads();
+        for (int k = 0; k < CL; ++k) {
+            if (part_ok[k]) continue;               // (the same for every thread: read from LDS after the barrier)
+            // partner k has not published: its pair from the logits themselves
+            const int64_t k0 = (int64_t)k * tiles_per_wg;
+            int64_t k1 = k0 + tiles_per_wg;
+            if (k1 > tn) k1 = tn;
+            const float* base = Z + (row / 256) * 65536 + (row % 256) * 256;
+            float mk = -INFINITY, sk = 0.f;
+            for (int64_t c = tid; c < (k1 - k0) * 64; c += NT) {
+                const int64_t tile = k0 + (c >> 6);
+                if (tile * 256 + (c & 63) * 4 < J)
+                    online_update(mk, sk, *reinterpret_cast<const floatx4*>(base + tile * tiles_m * 65536 + (c & 63) * 4));
+            }
+            const float Mk = block_max<NT>(mk, sm);
+            float Sk = block_sum<NT>(mk == -INFINITY ? 0.f : sk * expf(mk - Mk), sm);
+            if (Mk == -INFINITY) Sk = 1.0f;
+            if (tid == 0) {
+                part_m[k] = Mk;
+                part_s[k] = Sk;
+            }
+            __syncthreads();
+        }
+        float M = part_m[0];
+        for (int k = 1; k < CL; ++k) M = fmaxf(M, part_m[k]);
+        float S = 0.f;
+        for (int k = 0; k < CL; ++k) S += part_s[k] * expf(part_m[k] - M);
+        const float scale = expf(m_own - M) / S;
+
+        const int64_t out0 = row * J + t0 * 256;          // U index of class t0 * 256 of this row
+        // the label relative to this thread's first class of chunk 0 (|.| < 2^31: labels and J are 32-bit)
+        const int32_t lab_t = (int32_t)((int64_t)y[row] - t0 * 256) - (int32_t)j_thread;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            if (have & (1u << i)) {
+                floatx4 p;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) p[e] = v[i][e] * scale - ((lab_t == i * 4096 + e) ? 1.0f : 0.0f);
+                const u32x2 o = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3])};
+                __builtin_amdgcn_raw_buffer_store_b64(o, rsrc(U + out0 + i * 4096), j_thread * 2u, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < R; ++i) v[i] = vn[i];
+        __syncthreads();                            // part_m / part_s are rewritten in the next iteration
     }
 }
 
@@ -364,10 +533,52 @@ unsigned grid_for(int64_t n)
 
 }  // namespace
 
+// Cluster size of the one-read softmax for rows of J classes (tile-blocked logits), or 0 where the two-pass
+// kernel is used: short rows (the second pass then comes from the L2), J not a multiple of 4, rows too long for
+// 32 workgroups to hold.
+static int softmax_cluster(int64_t J)
+{
+    if (J < 65536 || J % 4 != 0) return 0;
+    const int64_t tn = (J + 255) / 256, per_wg = CLUSTER_CHUNKS * 1024 / 64;      // tile rows one workgroup holds
+    for (int cl = 2; cl <= 32; cl *= 2)
+        if ((tn + cl - 1) / cl <= per_wg) return cl;
+    return 0;
+}
+
+// Polls of a partner's word before a workgroup of the one-read softmax computes the partner's part itself
+// (about a microsecond each).  0: never wait (every workgroup then reads whole rows; for tests of that path).
+static int g_softmax_spin_limit = 1000;
+void set_softmax_spin_limit(int polls) { g_softmax_spin_limit = polls < 0 ? 1000 : polls; }
+
+int64_t mlr_softmax_scratch_bytes(int64_t B, int64_t J) { return softmax_cluster(J) ? B * softmax_cluster(J) * 8 : 0; }
+
 hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool out_bf16, int64_t B, int64_t J,
-                              hipStream_t stream, bool blocked)
+                              hipStream_t stream, bool blocked, void* scratch)
 {
     if (B <= 0 || J <= 0) return hipSuccess;
+    const int cl = (blocked && out_bf16 && B <= 65536) ? softmax_cluster(J) : 0;   // (32-bit offsets of a thread)
+    if (cl && scratch && reinterpret_cast<uintptr_t>(Z) % 16 == 0 && reinterpret_cast<uintptr_t>(U) % 16 == 0) {
+        static int cus = 0;
+        if (!cus) {
+            int dev = 0, n = 0;
+            hipError_t e = hipGetDevice(&dev);
+            if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e != hipSuccess) return e;
+            cus = n;
+        }
+        // one workgroup per CU so that all are resident together; whole clusters only
+        int grid = cus / cl * cl;
+        if (grid < cl) return hipErrorInvalidValue;
+        if ((int64_t)grid / cl > B) grid = (int)B * cl;
+        const int64_t tn = (J + 255) / 256;
+        const int tiles_per_wg = (int)((tn + cl - 1) / cl);
+        hipError_t e = launch_fill_u32(scratch, 0u, B * cl * 2, stream);
+        if (e != hipSuccess) return e;
+        unsigned long long* slots = static_cast<unsigned long long*>(scratch);
+        hipLaunchKernelGGL(mlr_softmax_cluster_kernel, dim3((unsigned)grid), dim3(1024), 0, stream, Z, y,
+                           static_cast<uint16_t*>(U), B, J, (B + 255) / 256, cl, tiles_per_wg, slots, g_softmax_spin_limit);
+        return hipGetLastError();
+    }
     // Vector path: rows of Z (and of U) must start 16-byte (8-byte for bf16 U) aligned.
     const int vec = (J % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0) &&
                     (reinterpret_cast<uintptr_t>(U) % 16 == 0);

@@ -131,6 +131,17 @@ int64_t sc_partial_bytes(int64_t B, int64_t J, int64_t D)
     return round_up(a > b ? a : b);
 }
 
+// Front of the workspace on the bf16 multiclass-logistic path: the tile-blocked logits, then the words the
+// workgroups of the one-read softmax exchange.
+int64_t bf16_logits_bytes(int64_t B, int64_t J)
+{
+    return round_up(sfb::mlr_logits_floats(B, J) * 4) + round_up(sfb::mlr_softmax_scratch_bytes(B, J));
+}
+void* bf16_softmax_scratch(sfb_ctx* ctx, int64_t B, int64_t J)
+{
+    return sfb::mlr_softmax_scratch_bytes(B, J) ? ctx->ws + round_up(sfb::mlr_logits_floats(B, J) * 4) : nullptr;
+}
+
 // True if W is currently kept as two planes by this context: its fp32 array is stale.
 bool is_split(const sfb_ctx* ctx, const float* W) { return ctx->split_lo && ctx->shadow_W == W; }
 
@@ -250,7 +261,7 @@ int64_t sfb_workspace_bytes(int32_t model, int64_t J, int64_t D, const sfb_batch
     switch (model) {
         case SFB_MLR:
             if (batch->in_dtype == SFB_BF16)   // logits (tile-blocked), aligned copy of X, bf16 copy of W
-                return round_up(sfb::mlr_logits_floats(B, J) * 4) + round_up(sfb::bf16_operand_bytes(B, D)) + sfb_shadow_bytes(J, D);
+                return bf16_logits_bytes(B, J) + round_up(sfb::bf16_operand_bytes(B, D)) + sfb_shadow_bytes(J, D);
             return round_up(B * J * 4) + round_up(sfb::gemm_f32_partial_bytes(B, J, D));   // logits, k-split scratch
         case SFB_DML:
             return round_up(B * J * 4) + round_up(sfb::gemm_f32_partial_bytes(B, J, D));   // projections Q[B][K], k-split scratch
@@ -388,7 +399,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
             SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, st));
             SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, false, B, J, st));
         } else {
-            uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + round_up(sfb::mlr_logits_floats(B, J) * 4));
+            uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + bf16_logits_bytes(B, J));
             const uint16_t* Wb = ctx->shadow_buf;
             if (!has_shadow) {   // no working copy attached: make one for this call
                 uint16_t* tmp = Xa + round_up(sfb::bf16_operand_bytes(B, D)) / 2;
@@ -397,7 +408,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
             }
             SFB_RUN(KID_FORWARD_BF16,
                     sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), Wb, Z, Xa, B, J, D, st));
-            SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true));
+            SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true, bf16_softmax_scratch(ctx, B, J)));
         }
         if (V && V != batch->X)
             SFB_RUN(KID_COPY, hipMemcpyAsync(V, batch->X, (size_t)(B * D * esz), hipMemcpyDeviceToDevice, st));
@@ -617,7 +628,7 @@ int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb
         return SFB_OK;
     }
     const int64_t pitch = sfb::bf16_pitch(D);
-    uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + round_up(sfb::mlr_logits_floats(B, J) * 4));
+    uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + bf16_logits_bytes(B, J));
     const uint16_t* Wb = ctx->shadow_buf;
     if (!has_shadow) {
         uint16_t* tmp = Xa + round_up(sfb::bf16_operand_bytes(B, D)) / 2;
@@ -627,7 +638,7 @@ int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb
     SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xa, 0u, sfb::bf16_operand_bytes(B, D) / 4, st));
     SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, true, nullptr, Xa, B, D, X->nnz, -pitch, 1, st));
     SFB_RUN(KID_FORWARD_BF16, sfb::launch_mlr_forward_bf16(nullptr, Wb, Z, Xa, B, J, D, st));
-    SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true));
+    SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true, bf16_softmax_scratch(ctx, B, J)));
     return SFB_OK;
 }
 
@@ -750,9 +761,6 @@ int sfb_last_hip_error(const sfb_ctx* ctx) { return ctx ? ctx->last_hip_error : 
 
 const char* sfb_version(void) { return "0.1"; }
 
-void sfb_tune_bf16_variant(int forward_variant, int apply_variant)
-{
-    sfb::set_bf16_variant(forward_variant, apply_variant);
-}
+void sfb_set_wait_limit(int polls) { sfb::set_softmax_spin_limit(polls); }
 
 }  // extern "C"

@@ -178,16 +178,72 @@ def test_mlr_peers_trajectory(ctx, sfb, oracle):
 # MLR, bf16 inputs / fp32 W and accumulate
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("J,D,B", [(520, 328, 200), (1000, 2056, 257), (8, 8, 1), (264, 10000, 130),
-                                   (40008, 264, 300)])   # last: 314 tiles, more than one per persistent workgroup
+                                   (40008, 264, 300),    # 314 tiles, more than one per persistent workgroup
+                                   # rows long enough for the softmax that reads the logits once, several
+                                   # workgroups per row: 2 per row with a ragged last tile; 4 per row, fewer rows
+                                   # than clusters; 8 per row, rows in more than one round
+                                   (70008, 136, 300), (160000, 72, 40), (170000, 72, 70)])
 def test_mlr_sf_bf16(ctx, sfb, oracle, J, D, B):
     print("mlr_sf_bf16", J, D, B, flush=True)
-    W0 = S.normal_matrix(J, D, 0.02, seed=3)
+    W0 = S.normal_matrix(J, D, 0.02 if J < 65536 else 0.2, seed=3)
     X, y = S.mlr_batch(J, D, B, seed=3, zero_frac=0.9, bf16=True)
+    if J >= 65536:
+        y[:4] = [0, J - 1, 255, 256]                  # labels at the ends of the row and of a tile
     U = torch.empty((B, J), dtype=torch.bfloat16, device="cuda:0")
     ctx.sfb_compute_sf(sfb.SFB_MLR, dev(W0), dev_bf16(X), Y=dev(y), U=U)
     Uo, _ = oracle.mlr_sf(W0, X, y)
-    assert rel_err(host(U), Uo) <= TOL_BF16
-    print("  err", rel_err(host(U), Uo), max_rel(host(U), Uo))
+    got = host(U).astype(np.float64)
+    assert rel_err(got, Uo) <= TOL_BF16
+    print("  err", rel_err(got, Uo), max_rel(got, Uo))
+    # The tolerance above is bf16's; a wrong normaliser of a row would hide under it.  Rounding errors average
+    # out over a row, so the least-squares factor between the two rows (label entry aside) must be 1 closely.
+    mask = np.ones_like(Uo, dtype=bool)
+    mask[np.arange(B), y] = False
+    factor = (np.where(mask, got * Uo, 0).sum(axis=1)) / (np.where(mask, Uo * Uo, 0).sum(axis=1))
+    print("  row factors", factor.min(), factor.max())
+    assert np.all(np.abs(factor - 1.0) < 2e-3)
+    lab = got[np.arange(B), y] - Uo[np.arange(B), y]
+    assert np.all(np.abs(lab) < 1e-2)                 # the label entry is p - 1: bf16 spacing 2^-8 near -1
+
+
+def test_mlr_softmax_partners_that_do_not_answer(sfb, oracle):
+    """Long rows are shared by several workgroups that exchange one pair per row; a workgroup whose partner
+    does not publish in time computes the partner's pair itself.  With a wait of zero polls every workgroup does
+    so (whether or not the pair arrives meanwhile), and the factors are those of the ordinary run to rounding; two
+    contexts whose kernels share the chip (neither set of workgroups is on it as a whole) finish with the same."""
+    J, D, B = 170000, 72, 70
+    W0 = S.normal_matrix(J, D, 0.2, seed=8)
+    X, y = S.mlr_batch(J, D, B, seed=8, zero_frac=0.9, bf16=True)
+    Uo, _ = oracle.mlr_sf(W0, X, y)
+    Wd, Xd, yd = dev(W0), dev_bf16(X), dev(y)
+    ca, cb = sfb.Context(0), sfb.Context(0)
+    ca.sfb_shadow_attach(Wd); cb.sfb_shadow_attach(Wd)          # (each context keeps its own working copy)
+    U0 = torch.empty((B, J), dtype=torch.bfloat16, device="cuda:0")
+    ca.sfb_compute_sf(sfb.SFB_MLR, Wd, Xd, Y=yd, U=U0)
+    torch.cuda.synchronize()
+    assert rel_err(host(U0), Uo) <= TOL_BF16
+    try:
+        sfb.sfb_set_wait_limit(0)
+        print("  zero polls", flush=True)
+        U1 = torch.empty_like(U0)
+        ca.sfb_compute_sf(sfb.SFB_MLR, Wd, Xd, Y=yd, U=U1)
+        torch.cuda.synchronize()
+    finally:
+        sfb.sfb_set_wait_limit(-1)
+    assert rel_err(host(U1), Uo) <= TOL_BF16
+    same = float((U1 == U0).float().mean())
+    print("  identical entries with and without waiting: %.6f" % same, flush=True)
+    assert same > 0.99 and rel_err(host(U1), host(U0)) <= 1e-2
+    print("  two contexts at once", flush=True)
+    Ua, Ub = torch.empty_like(U0), torch.empty_like(U0)
+    for _ in range(3):
+        ca.sfb_compute_sf(sfb.SFB_MLR, Wd, Xd, Y=yd, U=Ua)
+        cb.sfb_compute_sf(sfb.SFB_MLR, Wd, Xd, Y=yd, U=Ub)
+    torch.cuda.synchronize()
+    for U in (Ua, Ub):
+        assert rel_err(host(U), Uo) <= TOL_BF16
+        assert float((U == U0).float().mean()) > 0.99
+    ca.close(); cb.close()
 
 
 @pytest.mark.parametrize("N,J,D", [(1024, 520, 328), (100, 1000, 2056), (1, 8, 8), (77, 264, 136), (130, 128, 128),
