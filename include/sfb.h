@@ -81,9 +81,10 @@ int64_t sfb_apply_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dt
 
 /*
  * Optional bf16 working copy ("shadow") of one parameter matrix, for the bf16
- * multiclass-logistic path: fp32 master weights W plus a bf16 copy with
- * 128-byte-aligned rows that the forward contraction reads instead of W (half
- * the bytes, every request a whole cache line).  sfb_shadow_attach converts W
+ * multiclass-logistic path: fp32 master weights W plus a bf16 copy, laid out
+ * in the blocks the forward contraction streams, that it reads instead of W
+ * (half the bytes, every request a whole cache line; the layout inside the
+ * buffer is the library's business).  sfb_shadow_attach converts W
  * into the caller-allocated buffer (sfb_shadow_bytes, 256-byte aligned; the
  * library never frees it) and remembers (W, J, D).  While attached,
  *   - sfb_compute_sf(SFB_MLR, bf16) on that W reads the copy and needs
