@@ -353,11 +353,16 @@ def main():
     ctx.sfb_profile_collect()
     torch.cuda.synchronize()
     log("bench: timing %d steps" % args.steps)
+    # (one event per step boundary, recorded on the stream the library launches on: per-step durations)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
+    marks[0].record(ctx.stream)
     for i in range(args.steps):
         step(args.warmup + i)
+        marks[i + 1].record(ctx.stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     prof = ctx.sfb_profile_collect()
     ctx.sfb_profile_enable(False)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -459,6 +464,7 @@ def main():
                                + ("two 16-bit planes (hi = bf16 operand of the forward, lo = the other half of the fp32 word)"
                                   if split else "an fp32 array plus a bf16 working copy"),
                    "J": J, "D": D, "B": B, "rank1_terms_per_step": B},
+        "ms_per_step_events": {"median": per_step[len(per_step) // 2], "min": per_step[0], "max": per_step[-1]},
         "tflops_gemm_stages": 2 * gemm_flops / (ms_per_step * 1e-3) / 1e12,
         "mfma_frac_gemm_stages": 2 * gemm_flops / ((fwd_ms + app_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "stages": stages,
