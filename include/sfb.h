@@ -104,9 +104,10 @@ int sfb_shadow_detach(sfb_ctx* ctx);
 /*
  * Optional split storage of one parameter matrix, for the bf16 multiclass-logistic
  * path (instead of a working copy, not in addition to one).  The fp32 word of every
- * element is kept as two 16-bit halves in two separate planes: hi = (bits + 0x8000)
- * >> 16, which is the value rounded to bf16 (to nearest, ties away from zero), and
- * lo = bits & 0xffff; bits = (hi << 16) + sign_extend(lo) modulo 2^32, exactly.  Inside
+ * element is kept as two 16-bit halves in two separate planes, the halves of
+ * word = bits + 0x8000 (modulo 2^32): hi = word >> 16, which is the value rounded to
+ * bf16 (to nearest, ties away from zero), and lo = word & 0xffff; bits = ((hi << 16)
+ * | lo) - 0x8000, exactly.  Inside
  * the buffer the planes are laid out for the two kernels that stream them (hi in
  * blocks of 256 rows x 64 columns, lo in tiles of 256 x 256, each block one
  * contiguous piece); the layout is the library's business, the caller only provides

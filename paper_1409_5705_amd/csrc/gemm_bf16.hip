@@ -112,15 +112,18 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     return __builtin_bit_cast(uint32_t, h);
 }
 
-// A parameter matrix kept as two 16-bit planes: hi = (bits + 0x8000) >> 16 is the
-// value rounded to bf16 (to nearest, ties away from zero), lo = bits & 0xffff; the
-// fp32 bit pattern is (hi << 16) + sign_extend(lo) modulo 2^32, exactly.
-__device__ __forceinline__ float split_join(uint32_t hi16, uint32_t lo16)
-{
-    return __uint_as_float((hi16 << 16) + (uint32_t)(int32_t)(int16_t)(uint16_t)lo16);
-}
-__device__ __forceinline__ uint32_t split_hi(float v) { return (__float_as_uint(v) + 0x8000u) >> 16; }
-__device__ __forceinline__ uint32_t split_lo(float v) { return __float_as_uint(v) & 0xffffu; }
+// A parameter matrix kept as two 16-bit planes: the halves of word = bits + 0x8000 (modulo 2^32).  hi = word >> 16
+// is the value rounded to bf16 (to nearest, ties away from zero), lo = word & 0xffff; bits = ((hi << 16) | lo) -
+// 0x8000, exactly.  Two elements a dword in both planes: split_pair / join_pair move between the packed halves and
+// the two words with one byte permute each.
+__device__ __forceinline__ uint32_t split_word(float v) { return __float_as_uint(v) + 0x8000u; }
+__device__ __forceinline__ float split_value(uint32_t word) { return __uint_as_float(word - 0x8000u); }
+// words of elements 0 and 1 from their packed high halves h = [h1 : h0] and low halves l = [l1 : l0]
+__device__ __forceinline__ uint32_t join_pair0(uint32_t h, uint32_t l) { return __builtin_amdgcn_perm(h, l, 0x05040100u); }
+__device__ __forceinline__ uint32_t join_pair1(uint32_t h, uint32_t l) { return __builtin_amdgcn_perm(h, l, 0x07060302u); }
+// packed high halves [w1 >> 16 : w0 >> 16] and low halves [w1 & 0xffff : w0 & 0xffff] of two words
+__device__ __forceinline__ uint32_t pack_hi(uint32_t w0, uint32_t w1) { return __builtin_amdgcn_perm(w1, w0, 0x07060302u); }
+__device__ __forceinline__ uint32_t pack_lo(uint32_t w0, uint32_t w1) { return __builtin_amdgcn_perm(w1, w0, 0x05040100u); }
 
 // Element (r, c) of a bf16 operand of sf_gemm_kernel (and of the high plane): blocks of BM rows x BK columns
 // (one k-slice of a row tile, 32 KB in one piece), block (r / BM, c / BK) at index (r / BM) * (pitch / BK) + c / BK.
@@ -400,12 +403,12 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                     } else if (MODE == MODE_SPLIT) {
                         const uint32_t hA = w[q % EPD][e][0], hB = w[q % EPD][e][1], lA = w[q % EPD][e][2],
                                        lB = w[q % EPD][e][3];
-                        const float n0f = split_join(hA & 0xffffu, lA & 0xffffu) - p.eta * v0;
-                        const float n1f = split_join(hA >> 16, lA >> 16) - p.eta * v1;
-                        const float n2f = split_join(hB & 0xffffu, lB & 0xffffu) - p.eta * v2;
-                        const float n3f = split_join(hB >> 16, lB >> 16) - p.eta * v3;
-                        const u32x2 oh = {split_hi(n0f) | (split_hi(n1f) << 16), split_hi(n2f) | (split_hi(n3f) << 16)};
-                        const u32x2 ol = {split_lo(n0f) | (split_lo(n1f) << 16), split_lo(n2f) | (split_lo(n3f) << 16)};
+                        const uint32_t w0 = split_word(split_value(join_pair0(hA, lA)) - p.eta * v0);
+                        const uint32_t w1 = split_word(split_value(join_pair1(hA, lA)) - p.eta * v1);
+                        const uint32_t w2 = split_word(split_value(join_pair0(hB, lB)) - p.eta * v2);
+                        const uint32_t w3 = split_word(split_value(join_pair1(hB, lB)) - p.eta * v3);
+                        const u32x2 oh = {pack_hi(w0, w1), pack_hi(w2, w3)};
+                        const u32x2 ol = {pack_lo(w0, w1), pack_lo(w2, w3)};
                         // the high halves change only where the update crosses a bf16 rounding boundary: lanes
                         // whose four are unchanged leave the plane as it is (the same bits, fewer bytes written)
                         if (oh[0] != hA || oh[1] != hB)
@@ -633,10 +636,10 @@ __global__ __launch_bounds__(256) void split_from_w_kernel(const float* __restri
             const floatx4 a = *reinterpret_cast<const floatx4*>(W + r * cols + c);
             const floatx4 b = *reinterpret_cast<const floatx4*>(W + r * cols + c + 4);
             const float a0 = a[0], a1 = a[1], a2 = a[2], a3 = a[3], b0 = b[0], b1 = b[1], b2 = b[2], b3 = b[3];
-            h = u32x4{split_hi(a0) | (split_hi(a1) << 16), split_hi(a2) | (split_hi(a3) << 16),
-                      split_hi(b0) | (split_hi(b1) << 16), split_hi(b2) | (split_hi(b3) << 16)};
-            l = u32x4{split_lo(a0) | (split_lo(a1) << 16), split_lo(a2) | (split_lo(a3) << 16),
-                      split_lo(b0) | (split_lo(b1) << 16), split_lo(b2) | (split_lo(b3) << 16)};
+            const uint32_t w0 = split_word(a0), w1 = split_word(a1), w2 = split_word(a2), w3 = split_word(a3);
+            const uint32_t w4 = split_word(b0), w5 = split_word(b1), w6 = split_word(b2), w7 = split_word(b3);
+            h = u32x4{pack_hi(w0, w1), pack_hi(w2, w3), pack_hi(w4, w5), pack_hi(w6, w7)};
+            l = u32x4{pack_lo(w0, w1), pack_lo(w2, w3), pack_lo(w4, w5), pack_lo(w6, w7)};
         }
         *reinterpret_cast<u32x4*>(hi + operand_index(r, c, pitch)) = h;
         if (c < cols) *reinterpret_cast<u32x4*>(lo + split_lo_index(r, c, tiles_n)) = l;
@@ -653,10 +656,10 @@ __global__ __launch_bounds__(256) void w_from_split_kernel(const uint16_t* __res
         const u32x4 h = *reinterpret_cast<const u32x4*>(hi + operand_index(r, c, pitch));
         const u32x4 l = *reinterpret_cast<const u32x4*>(lo + split_lo_index(r, c, tiles_n));
         const uint32_t h0 = h[0], h1 = h[1], h2 = h[2], h3 = h[3], l0 = l[0], l1 = l[1], l2 = l[2], l3 = l[3];
-        const floatx4 a = {split_join(h0 & 0xffffu, l0 & 0xffffu), split_join(h0 >> 16, l0 >> 16),
-                           split_join(h1 & 0xffffu, l1 & 0xffffu), split_join(h1 >> 16, l1 >> 16)};
-        const floatx4 b = {split_join(h2 & 0xffffu, l2 & 0xffffu), split_join(h2 >> 16, l2 >> 16),
-                           split_join(h3 & 0xffffu, l3 & 0xffffu), split_join(h3 >> 16, l3 >> 16)};
+        const floatx4 a = {split_value(join_pair0(h0, l0)), split_value(join_pair1(h0, l0)),
+                           split_value(join_pair0(h1, l1)), split_value(join_pair1(h1, l1))};
+        const floatx4 b = {split_value(join_pair0(h2, l2)), split_value(join_pair1(h2, l2)),
+                           split_value(join_pair0(h3, l3)), split_value(join_pair1(h3, l3))};
         *reinterpret_cast<floatx4*>(W + r * cols + c) = a;
         *reinterpret_cast<floatx4*>(W + r * cols + c + 4) = b;
     }

@@ -77,7 +77,7 @@ hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64
                              const void* workspace, hipStream_t stream);
 // fp32 W[J][D] <-> planes hi (a J x D bf16 operand, bf16_operand_bytes(J, D)) and lo (split_lo_bytes(J, D)
 // bytes: 256 x 256 tiles in row-major tile order, one piece per workgroup of the apply):
-// bits = (hi << 16) + sign_extend(lo).
+// the halves of bits + 0x8000; bits = ((hi << 16) | lo) - 0x8000.
 int64_t split_lo_bytes(int64_t J, int64_t D);
 hipError_t launch_split_from_w(const float* W, uint16_t* hi, uint16_t* lo, int64_t J, int64_t D, hipStream_t stream);
 hipError_t launch_w_from_split(const uint16_t* hi, const uint16_t* lo, float* W, int64_t J, int64_t D, hipStream_t stream);
