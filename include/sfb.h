@@ -305,7 +305,7 @@ int sfb_profile_enable(sfb_ctx* ctx, int on);
 int sfb_profile_collect(sfb_ctx* ctx, sfb_kernel_time* out, int max_entries, int* count);
 
 /*
- * Bound of the only in-kernel wait of the library (process-wide).  For rows of
+ * Bound of the only in-kernel wait of the library (per context).  For rows of
  * 65536 classes or more the softmax of the bf16 multiclass-logistic path is
  * computed by several workgroups per row, each keeping its part of the row in
  * registers so that the logits are read once; they exchange one (max, sum) pair
@@ -314,8 +314,14 @@ int sfb_profile_collect(sfb_ctx* ctx, sfb_kernel_time* out, int max_entries, int
  * argument) and then computes that pair itself from the logits, so the result
  * never depends on which workgroups are on the chip together; 0 makes every
  * workgroup do so at once (same results; meant for tests of that path).
+ * sfb_wait_fallbacks waits for the context's stream and reports how many pairs
+ * workgroups have computed themselves in this way on the context's device since
+ * the library was loaded (all contexts of the device together): each costs a
+ * second read of the partner's part of the row, so a count that grows in
+ * normal operation says that kernels of other streams keep partners off the chip.
  */
-void sfb_set_wait_limit(int polls);
+int sfb_set_wait_limit(sfb_ctx* ctx, int polls);
+int sfb_wait_fallbacks(sfb_ctx* ctx, int64_t* count);
 
 #ifdef __cplusplus
 }

@@ -132,8 +132,10 @@ def lib():
         L.sfb_profile_collect.argtypes = [vp, ctypes.POINTER(sfb_kernel_time), ctypes.c_int,
                                           ctypes.POINTER(ctypes.c_int)]
         L.sfb_profile_collect.restype = ctypes.c_int
-        L.sfb_set_wait_limit.argtypes = [ctypes.c_int]
-        L.sfb_set_wait_limit.restype = None
+        L.sfb_set_wait_limit.argtypes = [vp, ctypes.c_int]
+        L.sfb_set_wait_limit.restype = ctypes.c_int
+        L.sfb_wait_fallbacks.argtypes = [vp, ctypes.POINTER(i64)]
+        L.sfb_wait_fallbacks.restype = ctypes.c_int
         L.sfb_ssp_create.argtypes = [ctypes.POINTER(vp), i32, i32]
         L.sfb_ssp_create.restype = ctypes.c_int
         L.sfb_ssp_destroy.argtypes = [vp]
@@ -164,10 +166,6 @@ def strerror(code: int) -> str:
 
 def version() -> str:
     return lib().sfb_version().decode()
-
-
-def sfb_set_wait_limit(polls: int = -1) -> None:
-    lib().sfb_set_wait_limit(int(polls))
 
 
 def _dtype_code(t: torch.Tensor) -> int:
@@ -260,6 +258,16 @@ class Context:
     def _check(self, rc, what):
         if rc != SFB_OK:
             raise SfbError(rc, what, lib().sfb_last_hip_error(self._h))
+
+    # -- the bounded wait of the softmax of long rows ----------------------------
+    def sfb_set_wait_limit(self, polls: int = -1):
+        self._check(lib().sfb_set_wait_limit(self._h, int(polls)), "sfb_set_wait_limit")
+
+    def sfb_wait_fallbacks(self) -> int:
+        """Partner pairs workgroups computed themselves so far on this device (waits for the stream)."""
+        n = ctypes.c_int64(0)
+        self._check(lib().sfb_wait_fallbacks(self._h, ctypes.byref(n)), "sfb_wait_fallbacks")
+        return int(n.value)
 
     # -- per-kernel timing ---------------------------------------------------
     def sfb_profile_enable(self, on=True):

@@ -41,9 +41,10 @@
 //     MFMA tiles of a lane hold four consecutive columns of C: the epilogue
 //     reads and writes C with 16-byte accesses (512 contiguous bytes per
 //     half-wave) without any cross-lane shuffle.
-//   * Workgroups are persistent (one per CU); ids are dealt round-robin to the 8
-//     XCDs (one L2 each): the 32 workgroups of an XCD walk 32 consecutive tiles
-//     of a raster in which tiles sharing operand panels are neighbours.
+//   * Workgroups are persistent (one per CU); ids are dealt round-robin to the
+//     XCDs (one L2 each; 8 of 32 CUs on MI355X, both read from the device): the
+//     workgroups of an XCD walk consecutive tiles of a raster in which tiles
+//     sharing operand panels are neighbours.
 #include "kernels.h"
 
 #include <type_traits>
@@ -59,7 +60,6 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int NUM_XCD = 8;
 constexpr int BK = 64;                   // k-slice: one 128-byte LDS row of bf16
 constexpr int BM = 256, BN = 256;        // workgroup tile
 constexpr int TM = 4, TN = 4;            // 32 x 32 MFMA tiles per wavefront (2 x 2 wavefronts)
@@ -103,6 +103,7 @@ struct Params {
     int tiles_m, tiles_n;
     int64_t tiles_total;
     int group_m;        // raster: groups of group_m row-tiles, row-tile index fastest inside a group
+    int num_xcd;        // XCDs of the device: consecutive workgroup ids go to consecutive XCDs
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
@@ -200,8 +201,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     const int wm0 = (wave >> 1) * (TM * 32), wn0 = (wave & 1) * (TN * 32);
 
     // ---- persistent schedule ------------------------------------------------
-    const int64_t x = blockIdx.x % NUM_XCD, wi = blockIdx.x / NUM_XCD, per_xcd = gridDim.x / NUM_XCD;
-    const int64_t q8 = p.tiles_total / NUM_XCD, r8 = p.tiles_total % NUM_XCD;
+    const int64_t x = blockIdx.x % p.num_xcd, wi = blockIdx.x / p.num_xcd, per_xcd = gridDim.x / p.num_xcd;
+    const int64_t q8 = p.tiles_total / p.num_xcd, r8 = p.tiles_total % p.num_xcd;
     const int64_t xcd_start = x * q8 + (x < r8 ? x : r8), xcd_cnt = q8 + (x < r8 ? 1 : 0);
     if (wi >= xcd_cnt) return;
     const int64_t n_my = (xcd_cnt - wi + per_xcd - 1) / per_xcd;   // tiles of this workgroup
@@ -666,8 +667,9 @@ __global__ __launch_bounds__(256) void w_from_split_kernel(const uint16_t* __res
 }
 
 template <int MODE>
-hipError_t launch(Params p, hipStream_t stream)
+hipError_t launch(Params p, DeviceInfo& dev, hipStream_t stream)
 {
+    if (dev.cus <= 0 || dev.xcds <= 0) return hipErrorInvalidDevice;
     p.tiles_m = (int)((p.M + BM - 1) / BM);
     p.tiles_n = (int)((p.N + BN - 1) / BN);
     p.tiles_total = (int64_t)p.tiles_m * p.tiles_n;
@@ -685,15 +687,19 @@ hipError_t launch(Params p, hipStream_t stream)
         return hipErrorInvalidValue;
     if (p.K <= 0 || p.K % BK != 0 || p.lda % BK != 0 || p.ldb % BK != 0 || p.lda < p.K || p.ldb < p.K)
         return hipErrorInvalidValue;
-    static bool attr_done = false;
-    if (!attr_done) {
+    if (!dev.gemm_bf16_lds_set[MODE]) {       // (per device: the caller's context holds the flag)
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sf_gemm_kernel<MODE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        dev.gemm_bf16_lds_set[MODE] = true;
     }
-    int64_t grid = 256;                      // one persistent workgroup per CU
-    if (p.tiles_total < grid) grid = (p.tiles_total + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+    p.num_xcd = dev.xcds;
+    int64_t grid = dev.cus / dev.xcds * dev.xcds;      // one persistent workgroup per CU, the same number per XCD
+    if (grid <= 0) {
+        grid = dev.cus;
+        p.num_xcd = 1;
+    }
+    if (p.tiles_total < grid) grid = (p.tiles_total + p.num_xcd - 1) / p.num_xcd * p.num_xcd;
     hipLaunchKernelGGL((sf_gemm_kernel<MODE>), dim3((unsigned)grid), dim3(NT), LDS_BYTES, stream, p);
     return hipGetLastError();
 }
@@ -719,7 +725,7 @@ hipError_t launch_shadow_from_w(const float* W, uint16_t* shadow, int64_t J, int
 }
 
 hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, float* Z, uint16_t* X_aligned,
-                                   int64_t B, int64_t J, int64_t D, hipStream_t stream)
+                                   int64_t B, int64_t J, int64_t D, DeviceInfo& dev, hipStream_t stream)
 {
     if (B <= 0 || J <= 0) return hipSuccess;
     const int64_t pitch = bf16_pitch(D);
@@ -736,7 +742,7 @@ hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, 
     p.c_blocked = 1;             // logits tile by tile: a workgroup writes 256 KB in one piece (see mlr_logits_floats)
     p.K = pitch;
     p.group_m = 0;               // all batch tiles of one class tile are neighbours (they share the W tile)
-    return launch<MODE_FWD>(p, stream);
+    return launch<MODE_FWD>(p, dev, stream);
 }
 
 // Floats of the tile-blocked logits array of launch_mlr_forward_bf16.
@@ -787,7 +793,7 @@ hipError_t launch_w_from_split(const uint16_t* hi, const uint16_t* lo, float* W,
 }
 
 hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64_t N, int64_t J, int64_t D, float eta,
-                             const void* workspace, hipStream_t stream)
+                             const void* workspace, DeviceInfo& dev, hipStream_t stream)
 {
     if (N <= 0 || J <= 0 || D <= 0) return hipSuccess;
     const int64_t Np = bf16_pitch(N);
@@ -803,9 +809,9 @@ hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64
     p.group_m = 8;               // 8 row-tiles x 4 column tiles under one L2 at a time (measured best of 1..32)
     if (W_lo) {
         p.lo = W_lo;
-        return launch<MODE_SPLIT>(p, stream);
+        return launch<MODE_SPLIT>(p, dev, stream);
     }
-    return launch<MODE_APPLY>(p, stream);
+    return launch<MODE_APPLY>(p, dev, stream);
 }
 
 }  // namespace sfb

@@ -6,6 +6,14 @@
 
 namespace sfb {
 
+// What the launchers need to know of the device a context is bound to; read once when the context is created.
+struct DeviceInfo {
+    int cus = 0;                                   // compute units
+    int xcds = 0;                                  // accelerator dies, one L2 each (workgroup ids go round-robin over them)
+    bool gemm_bf16_lds_set[3] = {false, false, false};   // dynamic-LDS attribute of sf_gemm_kernel<mode> set on this device
+    int softmax_wait_polls = 1000;                 // bound of the one-read softmax's wait for a partner's word
+};
+
 // ---------------------------------------------------------------------------
 // fp32 MFMA GEMM family:  acc[m][n] = sum_k A(m,k) * B(n,k), followed by an
 // epilogue that writes C[m*ldc + n].
@@ -58,7 +66,7 @@ hipError_t launch_shadow_from_w(const float* W, uint16_t* shadow, int64_t J, int
 // (j / 256) * ceil(B / 256) + b / 256, rows of 256 floats inside a tile; launch_mlr_softmax(..., blocked = true)
 // reads that layout.
 hipError_t launch_mlr_forward_bf16(const uint16_t* X, const uint16_t* W_shadow, float* Z, uint16_t* X_aligned,
-                                   int64_t B, int64_t J, int64_t D, hipStream_t stream);
+                                   int64_t B, int64_t J, int64_t D, DeviceInfo& dev, hipStream_t stream);
 // W[j][d] -= eta * sum_i U[i][j] * V[i][d];  U bf16 [N][J], V bf16 [N][D], W fp32 [J][D].
 // Two steps: launch_apply_bf16_transpose writes U^T and V^T into `workspace`
 // (apply_bf16_workspace_bytes, 256-byte aligned), launch_apply_bf16 consumes them.
@@ -74,7 +82,7 @@ hipError_t launch_apply_bf16_transpose(const uint16_t* U, const uint16_t* V, con
 // W_lo (nullable): W is kept as two 16-bit planes, W_shadow the high one (the value rounded
 // to bf16) and W_lo the low one; both are updated and the fp32 array W is not touched.
 hipError_t launch_apply_bf16(float* W, uint16_t* W_shadow, uint16_t* W_lo, int64_t N, int64_t J, int64_t D, float eta,
-                             const void* workspace, hipStream_t stream);
+                             const void* workspace, DeviceInfo& dev, hipStream_t stream);
 // fp32 W[J][D] <-> planes hi (a J x D bf16 operand, bf16_operand_bytes(J, D)) and lo (split_lo_bytes(J, D)
 // bytes: 256 x 256 tiles in row-major tile order, one piece per workgroup of the apply):
 // the halves of bits + 0x8000; bits = ((hi << 16) | lo) - 0x8000.
@@ -104,10 +112,14 @@ hipError_t launch_csr_check(const int64_t* indptr, const int32_t* indices, int64
 // scratch: mlr_softmax_scratch_bytes(B, J) bytes (8-byte aligned; contents irrelevant) or null; with it, blocked
 // logits of long rows are read once, by several workgroups per row that exchange their partial sums through it.
 int64_t mlr_softmax_scratch_bytes(int64_t B, int64_t J);
-// Polls of a partner's word before a workgroup of that kernel does the partner's part itself (< 0: default).
-void set_softmax_spin_limit(int polls);
+// dev (needed with scratch): CU count for the grid of that kernel, and the polls of a partner's word before a
+// workgroup does the partner's part itself.  Every such event is counted on the device (softmax_fallbacks).
 hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool out_bf16, int64_t B, int64_t J,
-                              hipStream_t stream, bool blocked = false, void* scratch = nullptr);
+                              hipStream_t stream, bool blocked = false, void* scratch = nullptr,
+                              const DeviceInfo* dev = nullptr);
+// Partner pairs that workgroups of the one-read softmax computed themselves instead of receiving them, on the
+// current device since the library was loaded (copies a device counter: the caller synchronises first).
+hipError_t softmax_fallbacks(unsigned long long* count);
 // V = X - Y (elementwise, n elements).
 hipError_t launch_diff(const float* X, const float* Y, float* V, int64_t n, hipStream_t stream);
 // DML coefficient: d = ||Q_i||^2; c = +2 (sim>0), -2 (sim<=0 and d<margin), else 0; U_i = c Q_i.

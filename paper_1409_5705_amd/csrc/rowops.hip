@@ -173,6 +173,8 @@ __global__ __launch_bounds__(NT) void mlr_softmax_kernel(const float* __restrict
 // has a non-zero high half: the bits of a sum that is at least 1).
 // ---------------------------------------------------------------------------
 constexpr int CLUSTER_CHUNKS = 10;        // 16-byte chunks of a row per thread
+// partner pairs computed by the waiting workgroup itself (one count per workgroup, row and partner)
+__device__ unsigned long long g_softmax_fallbacks = 0;
 
 __global__ __launch_bounds__(1024) void mlr_softmax_cluster_kernel(const float* __restrict__ Z,
                                                                   const int32_t* __restrict__ y,
@@ -296,6 +298,7 @@ __global__ __launch_bounds__(1024) void mlr_softmax_cluster_kernel(const float* 
             if (tid == 0) {
                 part_m[k] = Mk;
                 part_s[k] = Sk;
+                atomicAdd(&g_softmax_fallbacks, 1ull);
             }
             __syncthreads();
         }
@@ -553,29 +556,21 @@ static int softmax_cluster(int64_t J)
     return 0;
 }
 
-// Polls of a partner's word before a workgroup of the one-read softmax computes the partner's part itself
-// (about a microsecond each).  0: never wait (every workgroup then reads whole rows; for tests of that path).
-static int g_softmax_spin_limit = 1000;
-void set_softmax_spin_limit(int polls) { g_softmax_spin_limit = polls < 0 ? 1000 : polls; }
+hipError_t softmax_fallbacks(unsigned long long* count)
+{
+    return hipMemcpyFromSymbol(count, HIP_SYMBOL(g_softmax_fallbacks), sizeof(*count), 0, hipMemcpyDeviceToHost);
+}
 
 int64_t mlr_softmax_scratch_bytes(int64_t B, int64_t J) { return softmax_cluster(J) ? B * softmax_cluster(J) * 8 : 0; }
 
 hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool out_bf16, int64_t B, int64_t J,
-                              hipStream_t stream, bool blocked, void* scratch)
+                              hipStream_t stream, bool blocked, void* scratch, const DeviceInfo* dev)
 {
     if (B <= 0 || J <= 0) return hipSuccess;
     const int cl = (blocked && out_bf16 && B <= 65536) ? softmax_cluster(J) : 0;   // (32-bit offsets of a thread)
-    if (cl && scratch && reinterpret_cast<uintptr_t>(Z) % 16 == 0 && reinterpret_cast<uintptr_t>(U) % 16 == 0) {
-        static int cus = 0;
-        if (!cus) {
-            int dev = 0, n = 0;
-            hipError_t e = hipGetDevice(&dev);
-            if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-            if (e != hipSuccess) return e;
-            cus = n;
-        }
+    if (cl && scratch && dev && reinterpret_cast<uintptr_t>(Z) % 16 == 0 && reinterpret_cast<uintptr_t>(U) % 16 == 0) {
         // one workgroup per CU so that all are resident together; whole clusters only
-        int grid = cus / cl * cl;
+        int grid = dev->cus / cl * cl;
         if (grid < cl) return hipErrorInvalidValue;
         if ((int64_t)grid / cl > B) grid = (int)B * cl;
         const int64_t tn = (J + 255) / 256;
@@ -584,7 +579,7 @@ hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool ou
         if (e != hipSuccess) return e;
         unsigned long long* slots = static_cast<unsigned long long*>(scratch);
         hipLaunchKernelGGL(mlr_softmax_cluster_kernel, dim3((unsigned)grid), dim3(1024), 0, stream, Z, y,
-                           static_cast<uint16_t*>(U), B, J, (B + 255) / 256, cl, tiles_per_wg, slots, g_softmax_spin_limit);
+                           static_cast<uint16_t*>(U), B, J, (B + 255) / 256, cl, tiles_per_wg, slots, dev->softmax_wait_polls);
         return hipGetLastError();
     }
     // Vector path: rows of Z (and of U) must start 16-byte (8-byte for bf16 U) aligned.

@@ -60,7 +60,10 @@ struct sfb_ctx {
     int64_t shadow_J, shadow_D;
     // low plane when that matrix is kept as two 16-bit planes (sfb_split_attach); shadow_buf is then the high plane
     uint16_t* split_lo;
+    // CU / XCD counts of the device, per-device launch state, wait bound of the one-read softmax
+    sfb::DeviceInfo dev;
 };
+
 
 namespace {
 
@@ -169,6 +172,7 @@ int sfb_create(sfb_ctx** out, int device_id, void* hip_stream)
     if (hipGetDeviceCount(&count) != hipSuccess || device_id < 0 || device_id >= count) return SFB_EINVAL;
     sfb_ctx* c = new (std::nothrow) sfb_ctx;
     if (!c) return SFB_EINVAL;
+    (void)hipGetLastError();
     c->device = device_id;
     c->stream = reinterpret_cast<hipStream_t>(hip_stream);
     c->ws = nullptr;
@@ -183,6 +187,15 @@ int sfb_create(sfb_ctx** out, int device_id, void* hip_stream)
     c->shadow_buf = nullptr;
     c->shadow_J = c->shadow_D = 0;
     c->split_lo = nullptr;
+    int cus = 0, xcds = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device_id) != hipSuccess || cus <= 0) {
+        delete c;
+        return SFB_EHIP;
+    }
+    if (hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, device_id) != hipSuccess || xcds <= 0 || xcds > cus)
+        xcds = 1;   // unknown: one raster over all CUs (correct on any device, only the L2 locality is lost)
+    c->dev.cus = cus;
+    c->dev.xcds = xcds;
     *out = c;
     return SFB_OK;
 }
@@ -377,6 +390,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
     if (B == 0) return SFB_OK;
     if (!batch->X || !U || !aligned16(batch->X) || !aligned16(U) || (V && !aligned16(V))) return SFB_EINVAL;
     const bool has_shadow = ctx->shadow_buf && ctx->shadow_W == W && ctx->shadow_J == J && ctx->shadow_D == D;
+    if (is_split(ctx, W) && !has_shadow) return SFB_EINVAL;   // attached as planes of another shape: the fp32 array is stale
     int64_t need = sfb_workspace_bytes(model, J, D, batch);
     if (model == SFB_MLR && batch->in_dtype == SFB_BF16 && has_shadow) need -= sfb_shadow_bytes(J, D);
     if (need > 0 && (!ctx->ws || ctx->ws_bytes < need)) return SFB_ENOWS;
@@ -407,8 +421,8 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
                 Wb = tmp;
             }
             SFB_RUN(KID_FORWARD_BF16,
-                    sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), Wb, Z, Xa, B, J, D, st));
-            SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true, bf16_softmax_scratch(ctx, B, J)));
+                    sfb::launch_mlr_forward_bf16(static_cast<const uint16_t*>(batch->X), Wb, Z, Xa, B, J, D, ctx->dev, st));
+            SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true, bf16_softmax_scratch(ctx, B, J), &ctx->dev));
         }
         if (V && V != batch->X)
             SFB_RUN(KID_COPY, hipMemcpyAsync(V, batch->X, (size_t)(B * D * esz), hipMemcpyDeviceToDevice, st));
@@ -513,7 +527,7 @@ static int apply_impl(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* 
                 sfb::launch_apply_bf16_transpose(static_cast<const uint16_t*>(U), static_cast<const uint16_t*>(V), coef,
                                                  N, J, D, ctx->ws, ctx->stream));
         SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, Wb, is_split(ctx, W) ? ctx->split_lo : nullptr, N, J, D, eta,
-                                                       ctx->ws, ctx->stream));
+                                                       ctx->ws, ctx->dev, ctx->stream));
     }
     return SFB_OK;
 }
@@ -637,8 +651,8 @@ int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb
     }
     SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xa, 0u, sfb::bf16_operand_bytes(B, D) / 4, st));
     SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, true, nullptr, Xa, B, D, X->nnz, -pitch, 1, st));
-    SFB_RUN(KID_FORWARD_BF16, sfb::launch_mlr_forward_bf16(nullptr, Wb, Z, Xa, B, J, D, st));
-    SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true, bf16_softmax_scratch(ctx, B, J)));
+    SFB_RUN(KID_FORWARD_BF16, sfb::launch_mlr_forward_bf16(nullptr, Wb, Z, Xa, B, J, D, ctx->dev, st));
+    SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true, bf16_softmax_scratch(ctx, B, J), &ctx->dev));
     return SFB_OK;
 }
 
@@ -691,7 +705,7 @@ int sfb_apply_csr(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, c
     SFB_RUN(KID_APPLY_TRANSPOSE, sfb::launch_apply_bf16_transpose(static_cast<const uint16_t*>(U), nullptr, nullptr, N, J,
                                                                   D, ctx->ws, st));
     SFB_RUN(KID_APPLY_BF16, sfb::launch_apply_bf16(W, has_shadow ? ctx->shadow_buf : nullptr,
-                                                   is_split(ctx, W) ? ctx->split_lo : nullptr, N, J, D, eta, ctx->ws, st));
+                                                   is_split(ctx, W) ? ctx->split_lo : nullptr, N, J, D, eta, ctx->ws, ctx->dev, st));
     return SFB_OK;
 }
 
@@ -761,6 +775,22 @@ int sfb_last_hip_error(const sfb_ctx* ctx) { return ctx ? ctx->last_hip_error : 
 
 const char* sfb_version(void) { return "0.1"; }
 
-void sfb_set_wait_limit(int polls) { sfb::set_softmax_spin_limit(polls); }
+int sfb_set_wait_limit(sfb_ctx* ctx, int polls)
+{
+    if (!ctx) return SFB_EINVAL;
+    ctx->dev.softmax_wait_polls = polls < 0 ? 1000 : polls;
+    return SFB_OK;
+}
+
+int sfb_wait_fallbacks(sfb_ctx* ctx, int64_t* count)
+{
+    if (!ctx || !count) return SFB_EINVAL;
+    SFB_TRY(hipSetDevice(ctx->device));
+    SFB_TRY(hipStreamSynchronize(ctx->stream));
+    unsigned long long n = 0;
+    SFB_TRY(sfb::softmax_fallbacks(&n));
+    *count = (int64_t)n;
+    return SFB_OK;
+}
 
 }  // extern "C"

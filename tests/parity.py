@@ -39,3 +39,45 @@ def trajectory_check(Wg, Wref, W0, steps, tol):
     bound = tol * np.sqrt(np.mean(moved * moved)) + 2 * steps * np.spacing(np.float32(np.max(np.abs(Wref))))
     err = np.max(np.abs(Wg.astype(np.float64) - Wref))
     assert err <= bound, (err, bound)
+
+
+def mlr_u_check(got, ref, y, tol, factor_tol=None, label_tol=None):
+    """Checks MLR first factors U = softmax - onehot (rows of `got` against the oracle's `ref`, labels `y`).
+
+    A row holds one entry near -1 (the label) and J - 1 probabilities of order 1/J.  Taken over the whole row,
+    rms(r) is the label entry's (about 1/sqrt(J)), and rel_err would pass probabilities that are wrong by a
+    large factor.  So the label entry is compared on its own, the element-wise metric is taken with the label
+    entries masked out (its rms is then the probabilities' own), and the least-squares factor between the two
+    rows (label aside) must be 1: rounding errors average out over a row, a wrong normaliser or a wrong tile
+    does not.  Returns the masked element-wise error.
+    """
+    g = np.asarray(got, dtype=np.float64)
+    r = np.asarray(ref, dtype=np.float64)
+    assert g.shape == r.shape, (g.shape, r.shape)
+    B = r.shape[0]
+    if r.size == 0:
+        return 0.0
+    if factor_tol is None:
+        # bf16 output: every entry is off by at most 2^-9 of itself, so is their weighted mean; short rows
+        # average less.  fp32: a tenth of the element-wise tolerance.
+        factor_tol = (2e-3 if r.shape[1] >= 256 else 5e-3) if tol >= 1e-3 else 0.1 * tol
+    idx = np.arange(B)
+    y = np.asarray(y)
+    lab = np.abs(g[idx, y] - r[idx, y])
+    # the label entry is p - 1: spacing 2^-8 near -1 in bf16, 2^-24 in fp32
+    assert np.all(lab <= (label_tol if label_tol is not None else max(tol, 1e-6))), float(lab.max())
+    gm = g.copy()
+    rm = r.copy()
+    gm[idx, y] = 0.0
+    rm[idx, y] = 0.0
+    n = max(r.size - B, 1)
+    rms = np.sqrt(np.sum(rm * rm) / n)
+    den = np.abs(rm) + rms
+    den[den == 0.0] = 1.0
+    err = float(np.max(np.abs(gm - rm) / den))
+    assert err <= tol, (err, tol)
+    den_f = np.sum(rm * rm, axis=1)
+    ok = den_f > 0
+    factor = np.sum(gm * rm, axis=1)[ok] / den_f[ok]
+    assert np.all(np.abs(factor - 1.0) < factor_tol), (float(factor.min()), float(factor.max()))
+    return err

@@ -13,7 +13,7 @@ import numpy as np
 import pytest
 
 import sfb_synth as S
-from parity import TOL_BF16, TOL_F32, rel_err
+from parity import TOL_BF16, TOL_F32, mlr_u_check, rel_err, trajectory_check
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -52,7 +52,7 @@ def test_large_mlr_sf_sampled(big, sfb, oracle):
     print("large: compute_sf", flush=True)
     big["ctx"].sfb_compute_sf(sfb.SFB_MLR, big["W"], big["Xd"], Y=big["yd"], U=U)
     torch.cuda.synchronize()
-    rows = np.array([0, 1, 127, 128, 500, 777, 1022, 1023])
+    rows = np.array([0, 1, 255, 256, 300, 511, 512, 700, 767, 768, 1022, 1023])      # every 256-sample tile, both its ends
     print("large: W to host", flush=True)
     Wh = big["W"].cpu().numpy()
     print("large: oracle on %d samples" % len(rows), flush=True)
@@ -62,6 +62,10 @@ def test_large_mlr_sf_sampled(big, sfb, oracle):
     err = rel_err(Ug, Uo)
     print("large: U err", err, flush=True)
     assert err <= TOL_BF16
+    # all J classes of the sampled rows (every class tile), label entry apart: probabilities of ~3e-6 against
+    # their own rms, plus each row's least-squares factor
+    merr = mlr_u_check(Ug, Uo, big["y"][rows], TOL_BF16)
+    print("large: U err with the label entry masked", merr, flush=True)
     # the label entry and the zero-sum property on every sample (bf16 rounding of ~3e-6 entries)
     s = U.float().sum(dim=1).cpu().numpy()
     assert np.max(np.abs(s)) < 2e-2
@@ -143,3 +147,32 @@ def test_large_csr_entry_points_match_dense(big, sfb):
     ctx.sfb_apply_csr(Wb, U, ip, ix, vals, 1.0)
     torch.cuda.synchronize()
     assert torch.equal(Wa, Wb)
+
+
+@pytest.mark.timeout(600)
+def test_large_trajectory_reduced_d(sfb, oracle):
+    """The headline workload's 5 steps (eta = 0.001) with all 325,000 classes on the two planes, at a feature
+    count the host oracle can carry (D = 200: k ragged against the 64-wide slices; B = 512): SF computation and
+    application alternate, the oracle keeps W in fp64, factors and the final W are compared."""
+    J, B, eta, steps = CFG["J"], CFG["B"] // 2, CFG["eta"], CFG["steps"]
+    D = 200
+    W0 = S.normal_matrix(J, D, CFG["sigma"], seed=2)
+    W = torch.from_numpy(W0).to("cuda:0")
+    c = sfb.Context(0)
+    c.sfb_split_attach(W)
+    Wo = W0.astype(np.float64)
+    U = torch.empty((B, J), dtype=torch.bfloat16, device="cuda:0")
+    for step in range(steps):
+        X, y = S.mlr_batch(J, D, B, seed=2, step=step, zero_frac=CFG["zero_frac"], bf16=True)
+        Xd = torch.from_numpy(S.bf16_bits(X)).to("cuda:0").view(torch.bfloat16)
+        c.sfb_compute_sf(sfb.SFB_MLR, W, Xd, Y=torch.from_numpy(y).to("cuda:0"), U=U)
+        c.sfb_apply(W, U, Xd, eta)
+        torch.cuda.synchronize()
+        Uo, _ = oracle.mlr_sf(Wo, X, y)
+        err = mlr_u_check(U.float().cpu().numpy(), Uo, y, TOL_BF16, label_tol=1e-2)
+        print("large trajectory: step", step, "masked U err", err, flush=True)
+        Wo = oracle.apply(Wo, Uo, X, eta)
+    c.sfb_split_export(W)
+    torch.cuda.synchronize()
+    trajectory_check(W.cpu().numpy(), Wo, W0, steps, TOL_BF16)
+    c.close()

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 import sfb_synth as S
-from parity import TOL_BF16, TOL_F32, max_rel, rel_err
+from parity import TOL_BF16, TOL_F32, max_rel, mlr_u_check, rel_err
 from parity import trajectory_check as _trajectory_check
 
 torch = pytest.importorskip("torch")
@@ -114,6 +114,7 @@ def test_mlr_sf_f32(ctx, sfb, oracle, J, D, B):
     ctx.sfb_compute_sf(sfb.SFB_MLR, dev(W0), dev(X), Y=dev(y), U=U, V=V)
     Uo, Vo = oracle.mlr_sf(W0, X, y)
     assert rel_err(host(U), Uo) <= TOL_F32
+    mlr_u_check(host(U), Uo, y, TOL_F32)
     np.testing.assert_array_equal(host(V), X)
     assert np.max(np.abs(host(U).sum(axis=1))) < 1e-5
 
@@ -144,6 +145,7 @@ def test_mlr_small_trajectory(ctx, sfb, oracle):
         ctx.sfb_apply(W, U, Xd, eta)
         Uo, Vo = oracle.mlr_sf(Wo, X, y)
         assert rel_err(host(U), Uo) <= TOL_F32
+        mlr_u_check(host(U), Uo, y, TOL_F32)
         Wo = oracle.apply(Wo, Uo, Vo, eta)
     _trajectory_check(host(W), Wo, W0, c["steps"], TOL_F32)
 
@@ -152,7 +154,7 @@ def test_mlr_peers_trajectory(ctx, sfb, oracle):
     """Local batch plus 7 simulated peers' SF blocks, 2048 rank-1 terms a step."""
     c = S.CONFIGS["mlr_peers"]
     J, D, B, eta, P = c["J"], c["D"], c["B"], c["eta"], c["peers"]
-    steps = 4                                            # oracle time; the bench runs all 20
+    steps = c["steps"]                                   # all 20
     W0 = S.normal_matrix(J, D, c["sigma"], seed=0)
     W = dev(W0); Wo = W0.astype(np.float64)
     N = B * (P + 1)
@@ -169,6 +171,7 @@ def test_mlr_peers_trajectory(ctx, sfb, oracle):
         ctx.sfb_apply(W, Uall, Vall, eta)
         Uo, Vo = oracle.mlr_sf(Wo, X, y)
         assert rel_err(host(Uall[:B]), Uo) <= TOL_F32
+        mlr_u_check(host(Uall[:B]), Uo, y, TOL_F32)
         Ucat = np.concatenate([Uo] + [u for u, _ in peers]); Vcat = np.concatenate([Vo] + [v for _, v in peers])
         Wo = oracle.apply(Wo, Ucat, Vcat, eta)
     _trajectory_check(host(W), Wo, W0, steps, TOL_F32)
@@ -195,15 +198,9 @@ def test_mlr_sf_bf16(ctx, sfb, oracle, J, D, B):
     got = host(U).astype(np.float64)
     assert rel_err(got, Uo) <= TOL_BF16
     print("  err", rel_err(got, Uo), max_rel(got, Uo))
-    # The tolerance above is bf16's; a wrong normaliser of a row would hide under it.  Rounding errors average
-    # out over a row, so the least-squares factor between the two rows (label entry aside) must be 1 closely.
-    mask = np.ones_like(Uo, dtype=bool)
-    mask[np.arange(B), y] = False
-    factor = (np.where(mask, got * Uo, 0).sum(axis=1)) / (np.where(mask, Uo * Uo, 0).sum(axis=1))
-    print("  row factors", factor.min(), factor.max())
-    assert np.all(np.abs(factor - 1.0) < 2e-3)
-    lab = got[np.arange(B), y] - Uo[np.arange(B), y]
-    assert np.all(np.abs(lab) < 1e-2)                 # the label entry is p - 1: bf16 spacing 2^-8 near -1
+    # The tolerance above is bf16's and its scale the label entry's: the probabilities are checked against
+    # their own rms, each row's least-squares factor against 1, the label entry on its own.
+    print("  masked err", mlr_u_check(got, Uo, y, TOL_BF16, label_tol=1e-2))
 
 
 def test_mlr_softmax_partners_that_do_not_answer(sfb, oracle):
@@ -222,15 +219,19 @@ def test_mlr_softmax_partners_that_do_not_answer(sfb, oracle):
     ca.sfb_compute_sf(sfb.SFB_MLR, Wd, Xd, Y=yd, U=U0)
     torch.cuda.synchronize()
     assert rel_err(host(U0), Uo) <= TOL_BF16
-    try:
-        sfb.sfb_set_wait_limit(0)
-        print("  zero polls", flush=True)
-        U1 = torch.empty_like(U0)
-        ca.sfb_compute_sf(sfb.SFB_MLR, Wd, Xd, Y=yd, U=U1)
-        torch.cuda.synchronize()
-    finally:
-        sfb.sfb_set_wait_limit(-1)
+    mlr_u_check(host(U0), Uo, y, TOL_BF16, label_tol=1e-2)
+    before = ca.sfb_wait_fallbacks()
+    ca.sfb_set_wait_limit(0)
+    print("  zero polls", flush=True)
+    U1 = torch.empty_like(U0)
+    ca.sfb_compute_sf(sfb.SFB_MLR, Wd, Xd, Y=yd, U=U1)
+    torch.cuda.synchronize()
+    ca.sfb_set_wait_limit(-1)
+    counted = ca.sfb_wait_fallbacks() - before
+    print("  pairs computed by the waiting workgroup itself:", counted, flush=True)
+    assert counted >= 8 * 7                         # 8 workgroups a row, each does its 7 partners' parts (at least in its first row)
     assert rel_err(host(U1), Uo) <= TOL_BF16
+    mlr_u_check(host(U1), Uo, y, TOL_BF16, label_tol=1e-2)
     same = float((U1 == U0).float().mean())
     print("  identical entries with and without waiting: %.6f" % same, flush=True)
     assert same > 0.99 and rel_err(host(U1), host(U0)) <= 1e-2
@@ -242,6 +243,7 @@ def test_mlr_softmax_partners_that_do_not_answer(sfb, oracle):
     torch.cuda.synchronize()
     for U in (Ua, Ub):
         assert rel_err(host(U), Uo) <= TOL_BF16
+        mlr_u_check(host(U), Uo, y, TOL_BF16, label_tol=1e-2)
         assert float((U == U0).float().mean()) > 0.99
     ca.close(); cb.close()
 
@@ -281,6 +283,7 @@ def test_bf16_shadow_stays_current(sfb, oracle):
         if step == 2:
             Uo, _ = oracle.mlr_sf(host(Wb), X, y)
             assert rel_err(host(Ua), Uo) <= TOL_BF16
+            mlr_u_check(host(Ua), Uo, y, TOL_BF16, label_tol=1e-2)
         before = Wb.bfloat16()
         step_eta = eta if step != 1 else eta * 1e-4          # the small one leaves most bf16 values as they are
         ca.sfb_apply(Wa, Ua, Xd, step_eta); cb.sfb_apply(Wb, Ub, Xd, step_eta)
@@ -395,6 +398,34 @@ def test_dml_hinge_ties_by_hand(ctx, sfb, oracle):
     assert int(host(na)[0]) == no == 2
 
 
+@pytest.mark.parametrize("variant", ["stated", "half_active"])
+def test_dml_trajectory(ctx, sfb, oracle, variant):
+    """The metric-learning workload at its stated size and step count: 10 steps of SF computation +
+    application, a fresh batch of pairs per step, the oracle's W kept in fp64.  As stated (W ~ N(0, 0.01^2))
+    every hinge term is inactive; the second variant starts where about half of them are active."""
+    c = S.CONFIGS["dml"]
+    K, D, B, eta, steps = c["K"], c["D"], c["B"], c["eta"], c["steps"]
+    sigma = c["sigma"] if variant == "stated" else (2.0 * K * D) ** -0.5
+    W0 = S.normal_matrix(K, D, sigma, seed=0)
+    W = dev(W0); Wo = W0.astype(np.float64)
+    U = torch.empty((B, K), dtype=torch.float32, device="cuda:0")
+    V = torch.empty((B, D), dtype=torch.float32, device="cuda:0")
+    na = torch.zeros((1,), dtype=torch.int32, device="cuda:0")
+    for step in range(steps):
+        X, Y, sim = S.dml_batch(D, B, seed=0, step=step)
+        ctx.sfb_compute_sf(sfb.SFB_DML, W, dev(X), Y=dev(Y), sim=dev(sim), U=U, V=V, n_active=na, margin=c["margin"])
+        ctx.sfb_apply(W, U, V, eta)
+        Uo, Vo, no = oracle.dml_sf(Wo, X, Y, sim, margin=c["margin"])
+        d = np.sum(((X.astype(np.float64) - Y) @ Wo.T) ** 2, axis=1)
+        if np.min(np.abs(d[sim < 0] - c["margin"])) < 1e-4:
+            pytest.skip("a pair within rounding of the hinge's kink at step %d: the decision is not unique" % step)
+        print("  dml step", step, "active", no, flush=True)
+        assert int(host(na)[0]) == no
+        assert rel_err(host(U), Uo) <= TOL_F32
+        Wo = oracle.apply(Wo, Uo, Vo, eta)
+    _trajectory_check(host(W), Wo, W0, steps, TOL_F32)
+
+
 # ---------------------------------------------------------------------------
 # sparse coding
 # ---------------------------------------------------------------------------
@@ -437,6 +468,34 @@ def test_sc_full_step_with_prox(ctx, sfb, oracle):
         ref = oracle.prox_rows(W1, mode)
         assert rel_err(host(Wg), ref) <= TOL_F32
         assert np.max(np.linalg.norm(host(Wg).astype(np.float64), axis=1)) <= 1 + 1e-6
+
+
+@pytest.mark.timeout(600)
+def test_sc_trajectory(ctx, sfb, oracle):
+    """The sparse-coding workload at its stated dictionary size and step count: 5 steps of code solve,
+    W += eta U^T V and row projection, a fresh batch per step, against the oracle's fp64 trajectory.  The batch
+    is a quarter of the stated 512 samples (the oracle's un-blocked loops need about a minute per full batch;
+    the full batch is covered for one step by test_sc_full_step_with_prox)."""
+    c = S.CONFIGS["sc"]
+    J, D, eta, steps = c["J"], c["D"], c["eta"], c["steps"]
+    B = c["B"] // 4
+    W0 = S.sc_dictionary(J, D, seed=0)
+    W = dev(W0); Wo = W0.astype(np.float64)
+    U = torch.empty((B, J), dtype=torch.float32, device="cuda:0")
+    V = torch.empty((B, D), dtype=torch.float32, device="cuda:0")
+    for step in range(steps):
+        X = S.sc_batch(D, B, seed=0, step=step)
+        ctx.sfb_compute_sf(sfb.SFB_SC, W, dev(X), U=U, V=V, lam=c["lam"], ista_iters=c["ista_iters"],
+                           power_iters=c["power_iters"])
+        ctx.sfb_apply(W, U, V, -eta)
+        ctx.sfb_prox_rows(W, sfb.SFB_PROX_PROJECT)
+        Uo, Vo, L = oracle.sc_sf(Wo, X, lam=c["lam"], ista_iters=c["ista_iters"], power_iters=c["power_iters"])
+        print("  sc step", step, "L", L, "errs", rel_err(host(U), Uo), rel_err(host(V), Vo), flush=True)
+        assert rel_err(host(U), Uo) <= TOL_F32
+        assert rel_err(host(V), Vo) <= TOL_F32
+        Wo = oracle.prox_rows(oracle.apply(Wo, Uo, Vo, -eta), oracle.PROX_PROJECT)
+    _trajectory_check(host(W), Wo, W0, steps, TOL_F32)
+    assert np.max(np.linalg.norm(host(W).astype(np.float64), axis=1)) <= 1 + 1e-6
 
 
 def test_prox_rows(ctx, sfb, oracle):

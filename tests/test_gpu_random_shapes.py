@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 import sfb_synth as S
-from parity import TOL_BF16, TOL_F32, rel_err
+from parity import TOL_BF16, TOL_F32, mlr_u_check, rel_err, trajectory_check
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -73,6 +73,7 @@ def test_random_shape(sfb, oracle, case, kind, J, D, B, eta, copy):
             c.sfb_compute_sf(sfb.SFB_MLR, W, dev_bf16(X), Y=dev(y), U=U)
             Uo, _ = oracle.mlr_sf(W0, X, y)
             assert rel_err(host(U), Uo) <= TOL_BF16
+            mlr_u_check(host(U), Uo, y, TOL_BF16, label_tol=1e-2)
         elif kind in ("apply", "apply_split"):
             Uf = S.round_to_bf16((np.random.default_rng(case).standard_normal((B, J)) * 0.1).astype(np.float32))
             if kind == "apply_split":
@@ -84,8 +85,7 @@ def test_random_shape(sfb, oracle, case, kind, J, D, B, eta, copy):
                 c.sfb_split_export(W)
             ref = oracle.apply(W0.astype(np.float64), Uf, X, eta)
             # accumulation error of the update plus the fp32 rounding of the stored values
-            bound = 4 * TOL_F32 * np.sqrt(np.mean((ref - W0) ** 2)) + 2 * np.spacing(np.float32(np.max(np.abs(ref))))
-            assert float(np.max(np.abs(host(W) - ref))) <= bound
+            trajectory_check(host(W), ref, W0, 1, TOL_F32)
         else:
             c.sfb_split_attach(W)
             U = torch.empty((B, J), dtype=torch.bfloat16, device="cuda:0")
@@ -94,6 +94,7 @@ def test_random_shape(sfb, oracle, case, kind, J, D, B, eta, copy):
             c.sfb_apply(W, U, Xd, 0.05)
             c.sfb_split_export(W)
             Uo, _ = oracle.mlr_sf(W0, X, y)
+            mlr_u_check(host(U), Uo, y, TOL_BF16, label_tol=1e-2)
             ref = oracle.apply(W0.astype(np.float64), Uo, X, 0.05)
             assert rel_err(host(W) - W0, ref - W0) <= TOL_BF16
     finally:
@@ -135,6 +136,7 @@ def test_random_shape_f32(sfb, oracle, case, kind, J, D, B):
             c.sfb_compute_sf(sfb.SFB_MLR, dev(W0), dev(X), Y=dev(y), U=U)
             Uo, _ = oracle.mlr_sf(W0, X, y)
             assert rel_err(host(U), Uo) <= TOL_F32
+            mlr_u_check(host(U), Uo, y, TOL_F32)
         elif kind in ("apply", "signed"):
             U = g.standard_normal((B, J), dtype=np.float32)
             V = g.standard_normal((B, D), dtype=np.float32)

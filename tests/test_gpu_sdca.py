@@ -93,11 +93,15 @@ def test_sdca_trajectory(ctx, sfb, oracle):
     Wo = O.dual_to_primal_l2(Zo, lam)
     _trajectory_check(host(Wg), Wo, np.zeros((J, D)), steps, TOL_F32)
     _trajectory_check(host(Zg), Zo, np.zeros((J, D)), steps, TOL_F32)
-    assert rel_err(host(Pg), Po) <= TOL_F32 * steps
+    e_p = rel_err(host(Pg), Po)
+    print('  sdca trajectory: P err %.3g' % e_p, flush=True)
+    assert e_p <= TOL_F32
     assert rel_err(host(Ws), host(Wg)) <= 1e-5
     # Z = (1/N) U A^T with u_i = onehot(y_i) - p_i still holds on the GPU's own state
     Ug = np.eye(J)[y] - host(Pg).astype(np.float64)
-    assert rel_err(host(Zg), Ug.T @ A.astype(np.float64) / N) <= TOL_F32 * steps
+    e_z = rel_err(host(Zg), Ug.T @ A.astype(np.float64) / N)
+    print('  sdca trajectory: Z invariant err %.3g' % e_z, flush=True)
+    assert e_z <= TOL_F32
 
 
 def test_sdca_rejects_bad_arguments(ctx, sfb):

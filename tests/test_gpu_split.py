@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import sfb_synth as S
-from parity import TOL_BF16, TOL_F32, rel_err
+from parity import TOL_BF16, TOL_F32, mlr_u_check, rel_err, trajectory_check
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -103,7 +103,7 @@ def test_apply_on_planes_gives_the_bits_of_apply_on_fp32(sfb, oracle, N, J, D, k
         ref = W0.astype(np.float64)
         for eta in etas:
             ref = oracle.apply(ref, U, V, eta)
-        assert rel_err(host(Wb) - W0, ref - W0) <= TOL_F32 * 4
+        trajectory_check(host(Wb), ref, W0, len(etas), TOL_F32)
     ca.close(); cb.close()
 
 
@@ -121,6 +121,7 @@ def test_forward_on_the_high_plane(sfb, oracle, J, D, B):
     cb.sfb_compute_sf(sfb.SFB_MLR, Wb, dev_bf16(X), Y=dev(y), U=Ub)
     Uo, _ = oracle.mlr_sf(W0, X, y)
     assert rel_err(host(Ub), Uo) <= TOL_BF16
+    mlr_u_check(host(Ub), Uo, y, TOL_BF16, label_tol=1e-2)
     # the high plane differs from the round-to-nearest-even working copy only where the dropped half is an
     # exact tie: almost every factor is the same bf16 number
     same = float((Ua == Ub).float().mean())
@@ -150,6 +151,7 @@ def test_split_training_steps_against_the_oracle(sfb, oracle):
         c.sfb_compute_sf(sfb.SFB_MLR, W, Xd, Y=dev(y), U=U)
         c.sfb_apply(W, U, Xd, eta)
         Uo, _ = oracle.mlr_sf(Wo, X, y)
+        mlr_u_check(host(U), Uo, y, TOL_BF16, label_tol=1e-2)
         Wo = oracle.apply(Wo, Uo, X, eta)
     c.sfb_split_export(W)
     got = host(W)
@@ -164,7 +166,11 @@ def test_split_refuses_what_would_use_the_stale_array(sfb):
     c.sfb_split_attach(W)
     Uf = torch.zeros((B, J), device="cuda:0"); Vf = torch.zeros((B, D), device="cuda:0")
     y = torch.zeros((B,), dtype=torch.int32, device="cuda:0")
+    Xb = torch.zeros((B, D), dtype=torch.bfloat16, device="cuda:0")
+    Ub = torch.zeros((B, 8), dtype=torch.bfloat16, device="cuda:0")
     for call in (lambda: c.sfb_apply(W, Uf, Vf, 0.1),
+                 lambda: c.sfb_compute_sf(sfb.SFB_MLR, W[:8], Xb, Y=y, U=Ub),      # the attached pointer, another shape
+                 lambda: c.sfb_apply(W[:8], Ub, Xb, 0.1),
                  lambda: c.sfb_prox_rows(W),
                  lambda: c.sfb_compute_sf(sfb.SFB_MLR, W, Vf, Y=y, U=Uf),
                  lambda: c.sfb_sdca_mlr_sf(W, Vf, torch.full((B, J), 1.0 / J, device="cuda:0"), 0.1, 10, 1.0, Uf),
