@@ -64,7 +64,7 @@ def test_large_mlr_sf_sampled(big, sfb, oracle):
     assert err <= TOL_BF16
     # all J classes of the sampled rows (every class tile), label entry apart: probabilities of ~3e-6 against
     # their own rms, plus each row's least-squares factor
-    merr = mlr_u_check(Ug, Uo, big["y"][rows], TOL_BF16)
+    merr = mlr_u_check(Ug, Uo, big["y"][rows], TOL_BF16, factor_tol=1e-3, label_tol=1e-2)
     print("large: U err with the label entry masked", merr, flush=True)
     # the label entry and the zero-sum property on every sample (bf16 rounding of ~3e-6 entries)
     s = U.float().sum(dim=1).cpu().numpy()
@@ -169,7 +169,7 @@ def test_large_trajectory_reduced_d(sfb, oracle):
         c.sfb_apply(W, U, Xd, eta)
         torch.cuda.synchronize()
         Uo, _ = oracle.mlr_sf(Wo, X, y)
-        err = mlr_u_check(U.float().cpu().numpy(), Uo, y, TOL_BF16, label_tol=1e-2)
+        err = mlr_u_check(U.float().cpu().numpy(), Uo, y, TOL_BF16, factor_tol=1e-3, label_tol=1e-2)
         print("large trajectory: step", step, "masked U err", err, flush=True)
         Wo = oracle.apply(Wo, Uo, X, eta)
     c.sfb_split_export(W)

@@ -200,7 +200,7 @@ def test_mlr_sf_bf16(ctx, sfb, oracle, J, D, B):
     print("  err", rel_err(got, Uo), max_rel(got, Uo))
     # The tolerance above is bf16's and its scale the label entry's: the probabilities are checked against
     # their own rms, each row's least-squares factor against 1, the label entry on its own.
-    print("  masked err", mlr_u_check(got, Uo, y, TOL_BF16, label_tol=1e-2))
+    print("  masked err", mlr_u_check(got, Uo, y, TOL_BF16, factor_tol=2e-3 if J > 8 else None, label_tol=1e-2))
 
 
 def test_mlr_softmax_partners_that_do_not_answer(sfb, oracle):
@@ -474,11 +474,11 @@ def test_sc_full_step_with_prox(ctx, sfb, oracle):
 def test_sc_trajectory(ctx, sfb, oracle):
     """The sparse-coding workload at its stated dictionary size and step count: 5 steps of code solve,
     W += eta U^T V and row projection, a fresh batch per step, against the oracle's fp64 trajectory.  The batch
-    is a quarter of the stated 512 samples (the oracle's un-blocked loops need about a minute per full batch;
-    the full batch is covered for one step by test_sc_full_step_with_prox)."""
+    is the stated 512 samples (the oracle's un-blocked loops need a quarter of a minute per step on the GPU machine's
+    host cores)."""
     c = S.CONFIGS["sc"]
     J, D, eta, steps = c["J"], c["D"], c["eta"], c["steps"]
-    B = c["B"] // 4
+    B = c["B"]
     W0 = S.sc_dictionary(J, D, seed=0)
     W = dev(W0); Wo = W0.astype(np.float64)
     U = torch.empty((B, J), dtype=torch.float32, device="cuda:0")
