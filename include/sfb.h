@@ -49,7 +49,8 @@ typedef enum {
     SFB_OK = 0,
     SFB_EINVAL = -1, /* null pointer, bad shape, bad enum, misaligned pointer, unsupported dtype mix */
     SFB_ENOWS = -2,  /* workspace missing or smaller than sfb_workspace_bytes() */
-    SFB_EHIP = -3    /* a HIP call failed; sfb_last_hip_error() has the code */
+    SFB_EHIP = -3,   /* a HIP call failed; sfb_last_hip_error() has the code */
+    SFB_ETOOBIG = -4 /* sfb_apply_static: the scratch this shape needs exceeds SFB_STATIC_SCRATCH_BYTES */
 } sfb_status;
 
 /* One mini-batch.  Pointers are device pointers; the struct itself is host memory. */
@@ -177,6 +178,29 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
  */
 int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const void* V,
               int64_t N, int32_t sf_dtype, float eta);
+
+/*
+ * sfb_apply for callers that cannot allocate device memory and therefore cannot
+ * hand the library a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the
+ * same resulting bits as sfb_apply; the scratch (U^T and V^T of bf16 factors,
+ * the k-split partial sums of fp32 factors) lives in a static device array of
+ * SFB_STATIC_SCRATCH_BYTES inside the library instead of the context's workspace,
+ * which is neither needed nor touched.  Each GPU the library runs on holds its
+ * own copy of that array until the process ends; sfb_create resolves its address
+ * on the context's device.  The call allocates and frees nothing.
+ *   - Shapes whose scratch (sfb_apply_workspace_bytes) exceeds the array are
+ *     refused with SFB_ETOOBIG; nothing is enqueued.
+ *   - All contexts of one GPU share the array, and it keeps the last call's
+ *     contents (every call overwrites all it reads): calls that overlap in time
+ *     on one GPU - two streams, two host threads - race on it.  Calls on one
+ *     stream are ordered and safe.
+ *   - Other status codes as for sfb_apply; SFB_EHIP if the array's address could
+ *     not be resolved when the context was created.
+ */
+#define SFB_STATIC_SCRATCH_BYTES (32u << 20)
+int sfb_apply_static(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const void* V,
+                     int64_t N, int32_t sf_dtype, float eta);
 
 /*
  * The same with one coefficient per factor pair, for updates that are a short

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libsfb.so")
 SFB_MLR, SFB_DML, SFB_SC = 0, 1, 2
 SFB_F32, SFB_BF16 = 0, 1
 SFB_PROX_PROJECT, SFB_PROX_NORMALIZE = 0, 1
-SFB_OK, SFB_EINVAL, SFB_ENOWS, SFB_EHIP = 0, -1, -2, -3
+SFB_OK, SFB_EINVAL, SFB_ENOWS, SFB_EHIP, SFB_ETOOBIG = 0, -1, -2, -3, -4
+SFB_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class sfb_batch(ctypes.Structure):
@@ -99,6 +100,8 @@ def lib():
         L.sfb_compute_sf.restype = ctypes.c_int
         L.sfb_apply.argtypes = [vp, vp, i64, i64, vp, vp, i64, i32, ctypes.c_float]
         L.sfb_apply.restype = ctypes.c_int
+        L.sfb_apply_static.argtypes = [vp, vp, i64, i64, vp, vp, i64, i32, ctypes.c_float]
+        L.sfb_apply_static.restype = ctypes.c_int
         L.sfb_apply_signed_workspace_bytes.argtypes = [i64, i64, i64, i32]
         L.sfb_apply_signed_workspace_bytes.restype = i64
         L.sfb_apply_signed.argtypes = [vp, vp, i64, i64, vp, vp, vp, i64, i32, ctypes.c_float]
@@ -353,6 +356,16 @@ class Context:
         rc = lib().sfb_apply(self._h, _ptr(W, "W", dtype=torch.float32), J, D, _ptr(U, "U", shape=(N, J)),
                              _ptr(V, "V", shape=(N, D)), N, _dtype_code(U), float(eta))
         self._check(rc, "sfb_apply")
+
+    def sfb_apply_static(self, W, U, V, eta):
+        """sfb_apply on the library's static scratch: no workspace, nothing allocated (here or in the library)."""
+        J, D = W.shape
+        N = U.shape[0]
+        if U.dtype != V.dtype:
+            raise TypeError("U and V must share a dtype")
+        rc = lib().sfb_apply_static(self._h, _ptr(W, "W", dtype=torch.float32), J, D, _ptr(U, "U", shape=(N, J)),
+                                    _ptr(V, "V", shape=(N, D)), N, _dtype_code(U), float(eta))
+        self._check(rc, "sfb_apply_static")
 
     def sfb_apply_signed(self, W, U, V, coef, eta):
         """Enqueues W -= eta * sum_i coef_i u_i v_i^T (in place); coef: fp32 device tensor [N]."""

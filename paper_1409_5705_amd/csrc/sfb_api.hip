@@ -62,8 +62,14 @@ struct sfb_ctx {
     uint16_t* split_lo;
     // CU / XCD counts of the device, per-device launch state, wait bound of the one-read softmax
     sfb::DeviceInfo dev;
+    // this device's copy of the library's static scratch array (sfb_apply_static), resolved by sfb_create
+    char* static_scratch;
+    int static_scratch_err;
 };
 
+// Scratch of sfb_apply_static: one array per GPU the library runs on, held until the process ends.  In host
+// code the name is only a handle for hipGetSymbolAddress; kernels and copies get the address it returns.
+static __device__ __align__(256) unsigned char scratch[SFB_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -196,6 +202,16 @@ int sfb_create(sfb_ctx** out, int device_id, void* hip_stream)
         xcds = 1;   // unknown: one raster over all CUs (correct on any device, only the L2 locality is lost)
     c->dev.cus = cus;
     c->dev.xcds = xcds;
+    // the address of this device's copy of the static scratch array (each GPU has its own)
+    int prev = -1;
+    (void)hipGetDevice(&prev);
+    void* sp = nullptr;
+    hipError_t e = hipSetDevice(device_id);
+    if (e == hipSuccess) e = hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch));
+    c->static_scratch = e == hipSuccess ? static_cast<char*>(sp) : nullptr;
+    c->static_scratch_err = (int)e;
+    if (e != hipSuccess) (void)hipGetLastError();
+    if (prev >= 0 && prev != device_id) (void)hipSetDevice(prev);
     *out = c;
     return SFB_OK;
 }
@@ -551,6 +567,26 @@ int sfb_apply(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const
     return apply_impl(ctx, W, J, D, U, V, nullptr, N, sf_dtype, eta);
 }
 
+int sfb_apply_static(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, const void* V, int64_t N,
+                     int32_t sf_dtype, float eta)
+{
+    const int rc = check_apply_args(ctx, W, J, D, U, V, N, sf_dtype);
+    if (rc != SFB_OK || N == 0) return rc;
+    const int64_t need = sfb_apply_workspace_bytes(J, D, N, sf_dtype);
+    if (need < 0) return (int)need;
+    if (need > (int64_t)SFB_STATIC_SCRATCH_BYTES) return SFB_ETOOBIG;
+    if (!ctx->static_scratch) return hip_fail(ctx, (hipError_t)ctx->static_scratch_err);
+    // the same launches as sfb_apply, with the static array in the place of the caller's workspace
+    char* const ws = ctx->ws;
+    const int64_t ws_bytes = ctx->ws_bytes;
+    ctx->ws = ctx->static_scratch;
+    ctx->ws_bytes = (int64_t)SFB_STATIC_SCRATCH_BYTES;
+    const int out = apply_impl(ctx, W, J, D, U, V, nullptr, N, sf_dtype, eta);
+    ctx->ws = ws;
+    ctx->ws_bytes = ws_bytes;
+    return out;
+}
+
 int64_t sfb_apply_signed_workspace_bytes(int64_t J, int64_t D, int64_t N, int32_t sf_dtype)
 {
     const int64_t base = sfb_apply_workspace_bytes(J, D, N, sf_dtype);
@@ -767,6 +803,7 @@ const char* sfb_strerror(int code)
         case SFB_EINVAL: return "invalid argument (null/misaligned pointer, shape, enum or dtype combination)";
         case SFB_ENOWS: return "workspace missing or smaller than sfb_workspace_bytes()";
         case SFB_EHIP: return "a HIP call failed (see sfb_last_hip_error)";
+        case SFB_ETOOBIG: return "problem too large for the library's static scratch (SFB_STATIC_SCRATCH_BYTES)";
         default: return "unknown sfb status";
     }
 }
