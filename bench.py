@@ -32,30 +32,46 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def profile_traffic_bytes():
-    """Scaled FETCH_SIZE + WRITE_SIZE per launch, by kernel, from the committed rocprofv3 summary."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "mlr_large_bf16_rocprofv3.md")
-    out = {}
+def kernel_sources_sha256():
+    """Hash of the HIP sources the library is built from: the stamp that ties a counter profile to the kernels."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_1409_5705_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h", ".cpp")) and name != "peaks.hip":
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()
+
+
+def profile_traffic_bytes(profile="mlr_large_bf16_rocprofv3.md"):
+    """Scaled FETCH_SIZE + WRITE_SIZE per launch, by kernel, from the committed rocprofv3 summary, and whether
+    that summary was taken on the kernels of this tree (its `kernel_sources_sha256` line against the sources'
+    hash): counters of other kernels are not quoted."""
+    path = os.path.join(ROOT, "profiles", profile)
+    out, stamp = {}, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes "):      # "traffic_bytes <kernel> <bytes>"
                 _, name, val = line.split()
                 out[name] = float(val)
+            elif line.startswith("kernel_sources_sha256 "):
+                stamp = line.split()[1]
     except OSError:
         pass
-    return out
+    current = stamp is not None and stamp == kernel_sources_sha256()
+    return (out if current else {}), current
 
 
-def cpu_baseline_mlr(cfg, X, y, seed):
-    """The oracle, as it stands, on a bounded sample of the workload: the first Js classes
-    (softmax over those), all B samples, full D: SF compute + apply.  Scaled to the metric's
-    unit by Js/J (both stages are linear in the number of classes)."""
+def cpu_baseline_mlr(cfg, X, y, W_rows):
+    """The oracle, as it stands, on a bounded sample of the workload: the first Js classes of the
+    benchmark's own W (softmax over those), all B samples, full D: SF compute + apply.  Scaled to the
+    metric's unit by Js/J (both stages are linear in the number of classes)."""
     import numpy as np
     import oracle
-    import sfb_synth as S
     J, D, B = cfg["J"], cfg["D"], cfg["B"]
-    Js = min(J, 32768)
-    Ws = S.normal_matrix(Js, D, cfg["sigma"], seed)
+    Ws = W_rows
+    Js = Ws.shape[0]
     ys = (y % Js).astype(np.int32)
     t0 = time.perf_counter()
     U, V = oracle.mlr_sf(Ws, X, ys)
@@ -68,7 +84,7 @@ def cpu_baseline_mlr(cfg, X, y, seed):
         "unit": "updates/s",
         "cores": oracle.num_threads(),
         "kind": "oracle",
-        "sample": "first %d of %d classes (softmax over those), all %d samples, D=%d; one step = SF compute "
+        "sample": "first %d of %d rows of the benchmark's W (softmax over those classes), all %d samples, D=%d; one step = SF compute "
                   "(%.1f s) + apply (%.1f s); rate scaled by %d/%d" % (Js, J, B, D, t1 - t0, t2 - t1, Js, J),
     }
 
@@ -266,6 +282,12 @@ def main():
     ap.add_argument("--peaks", action="store_true",
                     help="first run the stand-alone MFMA-only / HBM-streaming probe (paper_1409_5705_amd/sfb_peaks) "
                          "and report what this GPU sustains next to the published peaks")
+    ap.add_argument("--no-other-layout", action="store_true",
+                    help="mlr_large_bf16: skip the few extra steps in the fp32 + working-copy layout that are reported "
+                         "beside the headline (ms_per_step_fp32_layout)")
+    ap.add_argument("--zero-frac", type=float, default=None,
+                    help="mlr_large_bf16: fraction of feature entries that are zero (default: the workload's 0.9); with "
+                         "--csr, 0.995 is the tf-idf-like density at which sfb_mlr_sf_csr goes over the stored entries")
     ap.add_argument("--csr", action="store_true",
                     help="mlr_large_bf16: hand the samples over as CSR rows (sfb_mlr_sf_csr / sfb_apply_csr)")
     args = ap.parse_args()
@@ -302,6 +324,7 @@ def main():
         sys.exit(2)
     cfg = S.CONFIGS[args.workload]
     J, D, B, eta = cfg["J"], cfg["D"], cfg["B"], cfg["eta"]
+    zero_frac = cfg["zero_frac"] if args.zero_frac is None else args.zero_frac
     dev = torch.device("cuda", 0)
     sfb.lib()
 
@@ -310,11 +333,12 @@ def main():
     gen.manual_seed(0)
     W = torch.randn((J, D), dtype=torch.float32, device=dev, generator=gen) * cfg["sigma"]
     n_batches = args.steps + args.warmup
-    Xs, ys, X0, y0 = [], [], None, None
+    Xs, ys, X0, y0, nnzs = [], [], None, None, []
     for s in range(min(n_batches, 4)):                     # a few distinct batches, cycled
-        X, y = S.mlr_batch(J, D, B, seed=0, step=s, zero_frac=cfg["zero_frac"], bf16=True)
+        X, y = S.mlr_batch(J, D, B, seed=0, step=s, zero_frac=zero_frac, bf16=True)
         if s == 0:
             X0, y0 = X, y
+        nnzs.append(int(np.count_nonzero(X)))
         if args.csr:
             ip, ix, v = S.csr_from_dense(X)
             Xs.append((torch.from_numpy(ip).to(dev), torch.from_numpy(ix).to(dev),
@@ -322,6 +346,7 @@ def main():
         else:
             Xs.append(torch.from_numpy(S.bf16_bits(X)).to(dev).view(torch.bfloat16))
         ys.append(torch.from_numpy(y).to(dev))
+    nnz_mean = float(sum(nnzs)) / (len(nnzs) * B)
     U = torch.empty((B, J), dtype=torch.bfloat16, device=dev)
     ctx = sfb.Context(0)
     split = args.layout == "split" and not args.no_shadow
@@ -392,7 +417,8 @@ def main():
     kt = {k: v[1] / v[0] for k, v in prof.items()}          # ms per launch
     if "shadow_convert" in kt:                                # no working copy attached: conversion is part of forward
         kt["mlr_forward_bf16"] += kt["shadow_convert"]
-    fwd_ms = kt.get("mlr_forward_bf16", float("nan"))
+    gather_ms = kt.get("csr_forward_gather")                 # CSR samples sparse enough for the route over stored entries
+    fwd_ms = kt.get("mlr_forward_bf16", gather_ms if gather_ms is not None else float("nan"))
     app_ms = kt.get("apply_bf16", float("nan"))
     tr_ms = kt.get("apply_bf16_transpose", float("nan"))
     smx_ms = kt.get("mlr_softmax", float("nan"))
@@ -416,10 +442,18 @@ def main():
                              "hbm_frac": tr_bytes / tr_ms / 1e6 / PEAK_HBM_GBS},
         # zero fill + scatter of the aligned X and of V^T from the CSR rows, per step (0 for dense input)
         "csr_to_operand": {"ms": (prof.get("csr_to_operand", (0, 0.0))[1] + prof.get("fill", (0, 0.0))[1]) / args.steps},
+        # forward over the stored entries of CSR samples (sfb_mlr_sf_csr's sparse route): HBM-bound, one pass over
+        # the bf16 image of W, the logits written, the re-laid entries read; 0 when the dense product ran
+        "forward_gather": ({"ms": gather_ms, "nnz_per_sample": nnz_mean,
+                            "hbm_gbs": (J * D * 2 + B * J * 4 + 4 * nnz_mean * B) / gather_ms / 1e6,
+                            "hbm_frac": (J * D * 2 + B * J * 4 + 4 * nnz_mean * B) / gather_ms / 1e6 / PEAK_HBM_GBS}
+                           if gather_ms is not None else {"ms": 0.0}),
         "apply_gemm": {"ms": app_ms, "tflops": gemm_flops / app_ms / 1e9,
                        "mfma_frac": gemm_flops / app_ms / 1e9 / PEAK_BF16_TFLOPS,
                        "hbm_gbs": app_bytes / app_ms / 1e6, "hbm_frac": app_bytes / app_ms / 1e6 / PEAK_HBM_GBS},
     }
+    if gather_ms is not None:
+        stages["forward_gemm"] = {"ms": 0.0, "note": "the dense product did not run: see forward_gather"}
     # Roofline of the dominant kernel.  At this shape the forward contraction is
     # MFMA-bound (845 flop/B); the apply is bound by whichever roof its flops per
     # algorithmic byte put it under (ridge: 312 flop/B; 250 with the fp32 array,
@@ -427,7 +461,7 @@ def main():
     # `traffic`: HBM-side bytes per launch of that kernel from the rocprofv3 --pmc
     # passes (FETCH_SIZE, WRITE_SIZE, scaled by the copy-kernel calibration) that
     # the committed summary under profiles/ records; null if it has no such line.
-    traffic = profile_traffic_bytes()
+    traffic, traffic_current = profile_traffic_bytes()
     if fwd_ms >= app_ms:
         roof = {"kernel": "sf_gemm_kernel<0> (forward)", "bound": "mfma", "achieved": stages["forward_gemm"]["tflops"],
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": stages["forward_gemm"]["mfma_frac"],
@@ -444,7 +478,8 @@ def main():
         roof["flop_per_algorithmic_byte"] = gemm_flops / app_bytes
         roof["algorithmic_bytes"] = app_bytes
         roof["bf16_image_groups_rewritten"] = rewritten
-    roof["traffic_unit"] = "bytes per launch (rocprofv3 --pmc, separate run; see profiles/)"
+    roof["traffic_unit"] = "bytes per launch (rocprofv3 --pmc, separate run; see profiles/)" if traffic_current else \
+        "null: the committed counter profile was taken on other kernel sources than this tree's"
 
     out = {
         "metric": "rank-1 SF updates applied/sec (SF compute + reconstruct/apply), MLR J=325k D=10k",
@@ -460,21 +495,36 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "mlr_large_bf16: MLR J=325000 D=10000 B=N=1024, bf16 X/U/V, fp32 W and accumulate, "
-                               "X ~ N(0,1) with 90% zeros stored " + ("as CSR rows" if args.csr else "dense") + ", eta=0.001; W kept as "
+                               "X ~ N(0,1) with %g%% zeros stored " % (100 * zero_frac) + ("as CSR rows" if args.csr else "dense") + ", eta=0.001; W kept as "
                                + ("two 16-bit planes (hi = bf16 operand of the forward, lo = the other half of the fp32 word)"
                                   if split else "an fp32 array plus a bf16 working copy"),
                    "J": J, "D": D, "B": B, "rank1_terms_per_step": B},
         "ms_per_step_events": {"median": per_step[len(per_step) // 2], "min": per_step[0], "max": per_step[-1]},
         "tflops_gemm_stages": 2 * gemm_flops / (ms_per_step * 1e-3) / 1e12,
-        "mfma_frac_gemm_stages": 2 * gemm_flops / ((fwd_ms + app_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "mfma_frac_gemm_stages": (2 * gemm_flops / ((fwd_ms + app_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if gather_ms is None
+                                  else gemm_flops / (app_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS),
         "stages": stages,
         "roofline": roof,
     }
     if args.measured_peaks is not None:
         out["measured_peaks"] = args.measured_peaks
+    if split and not args.no_other_layout:
+        # the same steps with W kept as an fp32 array plus bf16 working copy (the library's other layout), untimed
+        # set-up, a few timed steps: reported beside the headline, never as `value`
+        ctx.sfb_split_detach()
+        ctx.sfb_shadow_attach(W)
+        for i in range(2):
+            step(i)
+        torch.cuda.synchronize()
+        n2 = min(args.steps, 5)
+        t0 = time.perf_counter()
+        for i in range(n2):
+            step(2 + i)
+        torch.cuda.synchronize()
+        out["ms_per_step_fp32_layout"] = (time.perf_counter() - t0) * 1e3 / n2
     if not args.no_cpu_baseline:
         log("bench: timing the CPU oracle on a bounded sample")
-        out["cpu_baseline"] = cpu_baseline_mlr(cfg, X0, y0, seed=0)
+        out["cpu_baseline"] = cpu_baseline_mlr(cfg, X0, y0, W[:min(J, 32768)].cpu().numpy())
     print(json.dumps(out), flush=True)
 
 

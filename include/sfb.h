@@ -229,16 +229,25 @@ int sfb_apply_signed(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U
  *   values  [nnz]       of `dtype` (fp32, or bf16 as raw 16-bit words).
  * This is the form in which a sparse factor block is buffered and would be
  * sent: nnz * (4 + element size) + 8 * (rows + 1) bytes instead of rows * cols
- * elements.  The two calls below take it as it is; they write the dense,
- * tile-aligned operands of the contractions straight from it (no dense X or V
- * in the caller's memory), and the contractions themselves stay dense matrix
- * products: at some 10 % non-zeros and hundreds of rows every block of an
- * operand tile holds non-zeros, so there is no tile to skip.
+ * elements.  The two calls below take it as it is.
+ *
+ * sfb_mlr_sf_csr computes the logits W x_i by one of two routes, chosen from
+ * nnz, B, J and D (sfb_set_csr_route overrides the choice):
+ *   - over the stored entries only (work proportional to nnz * J, W read once;
+ *     the route of tf-idf-like data with a fraction of a per cent of non-zeros),
+ *   - or, where that would be slower (about one per cent of non-zeros and more
+ *     at a batch of a thousand samples), as the dense matrix product of the
+ *     dense entry point, whose aligned operand is written straight from the
+ *     CSR rows (no dense X in the caller's memory).
+ * sfb_apply_csr always writes its dense operand from the CSR rows and runs the
+ * dense contraction: with hundreds of factor pairs every column of W is touched
+ * by some pair, and the read-modify-write of W is the cost either way.
  *
  * A stored entry with a column outside [0, cols) or a row range outside
- * [0, nnz] is ignored (nothing is written out of bounds); rows with repeated
- * columns give an unspecified one of the repeated values.  sfb_csr_check
- * verifies the format on the device.
+ * [0, nnz] is ignored (nothing is written out of bounds); a row with repeated
+ * columns gives an unspecified result for that row (one of the repeated values
+ * on the dense route, their sum on the other).  sfb_csr_check verifies the
+ * format on the device.
  */
 typedef struct {
     const int64_t* indptr;
@@ -258,6 +267,10 @@ int sfb_csr_check(sfb_ctx* ctx, const sfb_csr* m, int64_t* violations);
  * the second factors are the rows of X themselves.  y: int32 labels [B]. */
 int64_t sfb_mlr_sf_csr_workspace_bytes(int64_t J, int64_t D, int64_t B, int32_t dtype);
 int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb_csr* X, const int32_t* y, void* U);
+/* Route of sfb_mlr_sf_csr on this context: 0 = chosen per call (the default), 1 = always the dense product,
+ * 2 = always over the stored entries (shapes that route cannot take still go the dense way).  For
+ * measurements and tests; results agree to rounding (different summation order). */
+int sfb_set_csr_route(sfb_ctx* ctx, int route);
 
 /* sfb_apply / sfb_apply_signed with the second factors given as CSR rows
  * (V->rows = N, V->cols = D, U [N][J] of V->dtype; coef may be NULL):

@@ -112,6 +112,8 @@ def lib():
         L.sfb_mlr_sf_csr_workspace_bytes.restype = i64
         L.sfb_mlr_sf_csr.argtypes = [vp, vp, i64, i64, ctypes.POINTER(sfb_csr), vp, vp]
         L.sfb_mlr_sf_csr.restype = ctypes.c_int
+        L.sfb_set_csr_route.argtypes = [vp, ctypes.c_int]
+        L.sfb_set_csr_route.restype = ctypes.c_int
         L.sfb_apply_csr_workspace_bytes.argtypes = [i64, i64, i64, i32]
         L.sfb_apply_csr_workspace_bytes.restype = i64
         L.sfb_apply_csr.argtypes = [vp, vp, i64, i64, vp, ctypes.POINTER(sfb_csr), vp, ctypes.c_float]
@@ -418,6 +420,10 @@ class Context:
         rc = lib().sfb_mlr_sf_csr(self._h, _ptr(W, "W", dtype=torch.float32), J, D, ctypes.byref(m),
                                   _ptr(y, "y (labels)", dtype=torch.int32, shape=(B,)), _ptr(U, "U", shape=(B, J)))
         self._check(rc, "sfb_mlr_sf_csr")
+
+    def sfb_set_csr_route(self, route: int = 0):
+        """0: sfb_mlr_sf_csr picks its route per call; 1: dense product; 2: over the stored entries."""
+        self._check(lib().sfb_set_csr_route(self._h, int(route)), "sfb_set_csr_route")
 
     def sfb_apply_csr(self, W, U, indptr, indices, values, eta, coef=None):
         """Enqueues W -= eta * sum_i coef_i u_i v_i^T with the v_i given as CSR rows (in place)."""

@@ -100,6 +100,16 @@ hipError_t launch_w_from_split(const uint16_t* hi, const uint16_t* lo, float* W,
 hipError_t launch_csr_scatter(const int64_t* indptr, const int32_t* indices, const void* values, bool bf16,
                               const float* coef, void* dst, int64_t rows, int64_t cols, int64_t nnz,
                               int64_t row_stride, int64_t col_stride, hipStream_t stream);
+// Logits z(b, j) = sum over the stored entries (d, x) of CSR row b of W(j, d) x, computed over the non-zeros only
+// (work proportional to nnz * J; W is read once).  bf16: W is a J x D bf16 operand (blocked layout above), Z the
+// tile-blocked logits array of launch_mlr_forward_bf16, values bf16; fp32: W row-major fp32 [J][D], Z row-major
+// [B][J], values fp32.  workspace: csr_gather_workspace_bytes(B, D, bf16) bytes, 256-byte aligned (the CSR rows
+// re-laid per 64-sample slice and column chunk).  csr_gather_supported: whether this shape can take that route.
+bool csr_gather_supported(int64_t B, int64_t J, int64_t D);
+int64_t csr_gather_workspace_bytes(int64_t B, int64_t D, bool bf16);
+hipError_t launch_csr_forward_gather(const int64_t* indptr, const int32_t* indices, const void* values, bool bf16,
+                                     const void* W, float* Z, int64_t B, int64_t J, int64_t D, int64_t nnz,
+                                     void* workspace, hipStream_t stream);
 // Adds the number of format violations to *bad (device, zeroed by the caller).
 hipError_t launch_csr_check(const int64_t* indptr, const int32_t* indices, int64_t rows, int64_t cols, int64_t nnz,
                             unsigned int* bad, hipStream_t stream);

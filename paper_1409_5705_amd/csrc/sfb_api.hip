@@ -28,6 +28,7 @@ enum KernelId : int {
     KID_SHADOW,
     KID_SCALE_ROWS,
     KID_CSR,
+    KID_CSR_GATHER,
     KID_SDCA,
     KID_DUAL_TO_PRIMAL,
     KID_COUNT
@@ -35,7 +36,7 @@ enum KernelId : int {
 static const char* const kKernelNames[KID_COUNT] = {
     "mlr_forward_bf16", "apply_bf16", "apply_bf16_transpose", "mlr_softmax", "gemm_f32_store", "gemm_f32_rmw(apply)", "gemm_f32_resid",
     "gemm_f32_shrink", "diff", "dml_scale", "fill", "prox_rows", "power_iteration", "copy", "shadow_convert", "scale_rows",
-    "csr_to_operand", "sdca_mlr", "dual_to_primal"};
+    "csr_to_operand", "csr_forward_gather", "sdca_mlr", "dual_to_primal"};
 
 struct ProfSpan {
     hipEvent_t t0, t1;
@@ -62,6 +63,8 @@ struct sfb_ctx {
     uint16_t* split_lo;
     // CU / XCD counts of the device, per-device launch state, wait bound of the one-read softmax
     sfb::DeviceInfo dev;
+    // route of sfb_mlr_sf_csr: 0 chosen from the number of stored entries, 1 dense contraction, 2 over the non-zeros
+    int csr_route;
     // this device's copy of the library's static scratch array (sfb_apply_static), resolved by sfb_create
     char* static_scratch;
     int static_scratch_err;
@@ -193,6 +196,7 @@ int sfb_create(sfb_ctx** out, int device_id, void* hip_stream)
     c->shadow_buf = nullptr;
     c->shadow_J = c->shadow_D = 0;
     c->split_lo = nullptr;
+    c->csr_route = 0;
     int cus = 0, xcds = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device_id) != hipSuccess || cus <= 0) {
         delete c;
@@ -630,6 +634,15 @@ int sfb_csr_check(sfb_ctx* ctx, const sfb_csr* m, int64_t* violations)
     return SFB_OK;
 }
 
+// Bytes of the operand region of sfb_mlr_sf_csr behind the logits: the aligned dense copy of X (dense route) or
+// the re-laid CSR rows (route over the non-zeros), whichever is larger.
+static int64_t csr_operand_bytes(int64_t J, int64_t D, int64_t B, bool bf16)
+{
+    const int64_t dense = bf16 ? round_up(sfb::bf16_operand_bytes(B, D)) : round_up(B * D * 4);
+    const int64_t gather = sfb::csr_gather_supported(B, J, D) ? round_up(sfb::csr_gather_workspace_bytes(B, D, bf16)) : 0;
+    return dense > gather ? dense : gather;
+}
+
 int64_t sfb_mlr_sf_csr_workspace_bytes(int64_t J, int64_t D, int64_t B, int32_t dtype)
 {
     if (!valid_dtype(dtype)) return SFB_EINVAL;
@@ -637,8 +650,35 @@ int64_t sfb_mlr_sf_csr_workspace_bytes(int64_t J, int64_t D, int64_t B, int32_t 
     b.B = B;
     b.in_dtype = b.sf_dtype = dtype;
     const int64_t base = sfb_workspace_bytes(SFB_MLR, J, D, &b);
-    if (base < 0 || dtype == SFB_BF16) return base;     // bf16: the aligned copy of X is written from the CSR rows
-    return base + round_up(B * D * 4);                   // fp32: dense X
+    if (base < 0) return base;
+    if (dtype == SFB_BF16)      // logits, exchange words, operand region, room for a bf16 copy of W
+        return base - round_up(sfb::bf16_operand_bytes(B, D)) + csr_operand_bytes(J, D, B, true);
+    return base + csr_operand_bytes(J, D, B, false);     // fp32: logits, k-split scratch, operand region
+}
+
+// Whether the logits of these CSR samples are computed over the stored entries only.  Measured on MI355X
+// (J = 325000, D = 10000, bf16): the gather kernel takes, per group of up to 1024 samples, one pass over W
+// (1.6 ms: 5e-13 s per element) plus 8.4e-11 s per class and stored entry of an average sample (a lane walks one
+// sample, so the time follows the entries per sample, not their total); the dense MFMA product runs at about
+// 1.45 PFLOP/s on ceil(B / 256) * 256 rows.  That puts the crossover near 1 % of non-zeros at B = 1024 and leaves
+// batches of 256 and fewer to the dense product at any density.  fp32: both routes are slower (twice the bytes of W,
+// twice the LDS reads per entry; the fp32 MFMA product runs at about 60 TFLOP/s), the gather route wins up to some 10 %.
+static bool csr_use_gather(const sfb_ctx* ctx, int64_t B, int64_t J, int64_t D, int64_t nnz, bool bf16)
+{
+    if (!sfb::csr_gather_supported(B, J, D) || ctx->csr_route == 1) return false;
+    if (ctx->csr_route == 2) return true;
+    const double groups = (double)((B + 1023) / 1024), per_sample = (double)nnz / (double)B;
+    const double gather = groups * ((bf16 ? 5e-13 : 1e-12) * (double)J * (double)D + (bf16 ? 8.4e-11 : 1.7e-10) * (double)J * per_sample);
+    const double rows = (double)((B + 255) / 256 * 256);
+    const double dense = 2.0 * rows * (double)J * (double)D / (bf16 ? 1.45e15 : 6e13);
+    return gather < dense;
+}
+
+int sfb_set_csr_route(sfb_ctx* ctx, int route)
+{
+    if (!ctx || route < 0 || route > 2) return SFB_EINVAL;
+    ctx->csr_route = route;
+    return SFB_OK;
 }
 
 int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb_csr* X, const int32_t* y, void* U)
@@ -661,33 +701,46 @@ int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb
     SFB_TRY(hipSetDevice(ctx->device));
     hipStream_t st = ctx->stream;
     float* Z = reinterpret_cast<float*>(ctx->ws);
+    const bool gather = csr_use_gather(ctx, B, J, D, X->nnz, bf16);
     if (!bf16) {
         const int64_t part = round_up(sfb::gemm_f32_partial_bytes(B, J, D));
-        float* Xd = reinterpret_cast<float*>(ctx->ws + round_up(B * J * 4) + part);
-        SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xd, 0u, B * D, st));
-        SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, false, nullptr, Xd, B, D, X->nnz, D, 1, st));
-        sfb::GemmF32Args g = {};
-        g.A = Xd; g.lda = D; g.a_kstrided = false;
-        g.B = W; g.ldb = D; g.b_kstrided = false;
-        g.C = Z; g.ldc = J;
-        g.M = B; g.N = J; g.K = D;
-        g.epilogue = sfb::EPI_STORE;
-        if (part > 0) g.partial = reinterpret_cast<float*>(ctx->ws + round_up(B * J * 4));
-        SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, st));
+        char* region = ctx->ws + round_up(B * J * 4) + part;
+        if (gather) {
+            SFB_RUN(KID_CSR_GATHER, sfb::launch_csr_forward_gather(X->indptr, X->indices, X->values, false, W, Z, B, J, D,
+                                                                   X->nnz, region, st));
+        } else {
+            float* Xd = reinterpret_cast<float*>(region);
+            SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xd, 0u, B * D, st));
+            SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, false, nullptr, Xd, B, D, X->nnz, D, 1, st));
+            sfb::GemmF32Args g = {};
+            g.A = Xd; g.lda = D; g.a_kstrided = false;
+            g.B = W; g.ldb = D; g.b_kstrided = false;
+            g.C = Z; g.ldc = J;
+            g.M = B; g.N = J; g.K = D;
+            g.epilogue = sfb::EPI_STORE;
+            if (part > 0) g.partial = reinterpret_cast<float*>(ctx->ws + round_up(B * J * 4));
+            SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, st));
+        }
         SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, false, B, J, st));
         return SFB_OK;
     }
     const int64_t pitch = sfb::bf16_pitch(D);
-    uint16_t* Xa = reinterpret_cast<uint16_t*>(ctx->ws + bf16_logits_bytes(B, J));
+    char* region = ctx->ws + bf16_logits_bytes(B, J);
     const uint16_t* Wb = ctx->shadow_buf;
     if (!has_shadow) {
-        uint16_t* tmp = Xa + round_up(sfb::bf16_operand_bytes(B, D)) / 2;
+        uint16_t* tmp = reinterpret_cast<uint16_t*>(region + csr_operand_bytes(J, D, B, true));
         SFB_RUN(KID_SHADOW, sfb::launch_shadow_from_w(W, tmp, J, D, st));
         Wb = tmp;
     }
-    SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xa, 0u, sfb::bf16_operand_bytes(B, D) / 4, st));
-    SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, true, nullptr, Xa, B, D, X->nnz, -pitch, 1, st));
-    SFB_RUN(KID_FORWARD_BF16, sfb::launch_mlr_forward_bf16(nullptr, Wb, Z, Xa, B, J, D, ctx->dev, st));
+    if (gather) {
+        SFB_RUN(KID_CSR_GATHER, sfb::launch_csr_forward_gather(X->indptr, X->indices, X->values, true, Wb, Z, B, J, D, X->nnz,
+                                                               region, st));
+    } else {
+        uint16_t* Xa = reinterpret_cast<uint16_t*>(region);
+        SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xa, 0u, sfb::bf16_operand_bytes(B, D) / 4, st));
+        SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, true, nullptr, Xa, B, D, X->nnz, -pitch, 1, st));
+        SFB_RUN(KID_FORWARD_BF16, sfb::launch_mlr_forward_bf16(nullptr, Wb, Z, Xa, B, J, D, ctx->dev, st));
+    }
     SFB_RUN(KID_SOFTMAX, sfb::launch_mlr_softmax(Z, y, U, true, B, J, st, true, bf16_softmax_scratch(ctx, B, J), &ctx->dev));
     return SFB_OK;
 }

@@ -46,24 +46,37 @@ def csr_dev(X, bf16):
     return (indptr, indices, values), (dev(indptr), dev(indices), dev_vals(values, bf16))
 
 
+@pytest.mark.parametrize("route", [1, 2])                  # 1: dense product on operands written from the CSR rows; 2: over the stored entries
 @pytest.mark.parametrize("J,D,B,bf16,zero_frac", [
     (64, 128, 32, False, 0.9),
     (1000, 2048, 256, False, 0.9),
     (37, 50, 7, False, 0.5),        # nothing aligned
+    (1000, 7000, 300, False, 0.99), # 1 % non-zeros; three column chunks; J not a multiple of the 32-class groups
     (520, 328, 200, True, 0.9),
-    (264, 10000, 130, True, 0.9),   # the headline's feature count
+    (264, 10000, 130, True, 0.9),   # the headline's feature count: four column chunks
     (40008, 264, 300, True, 0.97),  # several tiles per workgroup; some samples nearly empty
+    (2056, 10000, 1100, True, 0.998),   # 0.2 % non-zeros; more samples than one group of 1024, last slice ragged
+    (70008, 1000, 130, True, 0.99),     # 1 % non-zeros; rows long enough for the softmax that shares a row
 ])
-def test_mlr_sf_csr(ctx, sfb, oracle, J, D, B, bf16, zero_frac):
-    print("mlr_sf_csr", J, D, B, bf16, flush=True)
-    W0 = S.normal_matrix(J, D, 0.02, seed=5)
+def test_mlr_sf_csr(ctx, sfb, oracle, J, D, B, bf16, zero_frac, route):
+    print("mlr_sf_csr", J, D, B, bf16, zero_frac, "route", route, flush=True)
+    W0 = S.normal_matrix(J, D, 0.02 if zero_frac < 0.98 else 0.2, seed=5)
     X, y = S.mlr_batch(J, D, B, seed=5, zero_frac=zero_frac, bf16=bf16)
     X[B // 2] = 0.0                                            # one sample without any non-zero
     (indptr, indices, values), (ip, ix, vals) = csr_dev(X, bf16)
     dt = torch.bfloat16 if bf16 else torch.float32
     U = torch.empty((B, J), dtype=dt, device="cuda:0")
     assert ctx.sfb_csr_check(ip, ix, vals, D) == 0
-    ctx.sfb_mlr_sf_csr(dev(W0), ip, ix, vals, dev(y), U)
+    ctx.sfb_set_csr_route(route)
+    try:
+        ctx.sfb_profile_enable(True)
+        ctx.sfb_profile_collect()
+        ctx.sfb_mlr_sf_csr(dev(W0), ip, ix, vals, dev(y), U)
+        ran = ctx.sfb_profile_collect()
+    finally:
+        ctx.sfb_profile_enable(False)
+        ctx.sfb_set_csr_route(0)
+    assert ("csr_forward_gather" in ran) == (route == 2), ran      # the route asked for is the one that ran
     Uo = oracle.mlr_sf_csr(W0, indptr, indices, values, y)
     err = rel_err(host(U), Uo)
     print("  err", err, flush=True)
@@ -72,10 +85,34 @@ def test_mlr_sf_csr(ctx, sfb, oracle, J, D, B, bf16, zero_frac):
         mlr_u_check(host(U), Uo, y, TOL_BF16, label_tol=1e-2)
     else:
         mlr_u_check(host(U), Uo, y, TOL_F32)
-    # same kernels on the same operand values as the dense entry point: same bits
     Ud = torch.empty_like(U)
     ctx.sfb_compute_sf(sfb.SFB_MLR, dev(W0), dev_vals(X, bf16).reshape(B, D), Y=dev(y), U=Ud)
-    assert torch.equal(U, Ud)
+    if route == 1:
+        # same kernels on the same operand values as the dense entry point: same bits
+        assert torch.equal(U, Ud)
+    else:
+        # another summation order: the same numbers up to the rounding of the output type
+        same = float((U == Ud).float().mean())
+        print("  entries identical to the dense route's: %.4f" % same, flush=True)
+        assert rel_err(host(U), host(Ud)) <= (TOL_BF16 if bf16 else TOL_F32)
+        assert not bf16 or same > 0.9
+
+
+def test_mlr_sf_csr_picks_its_route(ctx, sfb):
+    """Left to itself, the call goes over the stored entries at a fraction of a per cent of non-zeros and through
+    the dense product at ten per cent."""
+    J, D, B = 4096, 4096, 512
+    W = dev(S.normal_matrix(J, D, 0.02, seed=9))
+    U = torch.empty((B, J), dtype=torch.bfloat16, device="cuda:0")
+    for zero_frac, want in ((0.998, True), (0.9, False)):
+        X, y = S.mlr_batch(J, D, B, seed=9, zero_frac=zero_frac, bf16=True)
+        _, (ip, ix, vals) = csr_dev(X, True)
+        ctx.sfb_profile_enable(True)
+        ctx.sfb_profile_collect()
+        ctx.sfb_mlr_sf_csr(W, ip, ix, vals, dev(y), U)
+        ran = ctx.sfb_profile_collect()
+        ctx.sfb_profile_enable(False)
+        assert ("csr_forward_gather" in ran) == want, (zero_frac, ran)
 
 
 @pytest.mark.parametrize("N,J,D,bf16,zero_frac,signed", [

@@ -176,3 +176,46 @@ def test_large_trajectory_reduced_d(sfb, oracle):
     torch.cuda.synchronize()
     trajectory_check(W.cpu().numpy(), Wo, W0, steps, TOL_BF16)
     c.close()
+
+
+@pytest.mark.timeout(600)
+def test_large_csr_forward_over_stored_entries(big, sfb, oracle):
+    """At the headline shape with tf-idf-like sparsity (0.5 % of the features non-zero) sfb_mlr_sf_csr goes over
+    the stored entries (W streamed once); its factors against the oracle's loop over the same entries on sampled
+    rows, and against the dense route on all of them."""
+    J, D, B = big["J"], big["D"], big["B"]
+    X, y = S.mlr_batch(J, D, B, seed=3, zero_frac=0.995, bf16=True)
+    indptr, indices, values = S.csr_from_dense(X)
+    ip = torch.from_numpy(indptr).to("cuda:0")
+    ix = torch.from_numpy(indices).to("cuda:0")
+    vals = torch.from_numpy(S.bf16_bits(values)).to("cuda:0").view(torch.bfloat16)
+    yd = torch.from_numpy(y).to("cuda:0")
+    ctx = big["ctx"]
+    Ug = torch.empty((B, J), dtype=torch.bfloat16, device="cuda:0")
+    Ud = torch.empty_like(Ug)
+    ctx.sfb_profile_enable(True)
+    ctx.sfb_profile_collect()
+    ctx.sfb_mlr_sf_csr(big["W"], ip, ix, vals, yd, Ug)              # route left to the library
+    ran = ctx.sfb_profile_collect()
+    ctx.sfb_profile_enable(False)
+    print("large csr: kernels", ran, flush=True)
+    assert "csr_forward_gather" in ran
+    ctx.sfb_set_csr_route(1)
+    ctx.sfb_mlr_sf_csr(big["W"], ip, ix, vals, yd, Ud)
+    ctx.sfb_set_csr_route(0)
+    torch.cuda.synchronize()
+    same = float((Ug == Ud).float().mean())
+    print("large csr: entries identical to the dense route's: %.5f" % same, flush=True)
+    assert same > 0.99
+    rows = np.array([0, 255, 256, 511, 700, 1023])
+    Wh = big["W"].cpu().numpy()
+    sub_ptr = np.zeros(len(rows) + 1, dtype=np.int64)
+    sub_idx, sub_val = [], []
+    for k, r in enumerate(rows):
+        sub_idx.append(indices[indptr[r]:indptr[r + 1]]); sub_val.append(values[indptr[r]:indptr[r + 1]])
+        sub_ptr[k + 1] = sub_ptr[k] + len(sub_idx[-1])
+    Uo = oracle.mlr_sf_csr(Wh, sub_ptr, np.concatenate(sub_idx), np.concatenate(sub_val), y[rows])
+    del Wh
+    got = Ug[torch.from_numpy(rows).to("cuda:0")].float().cpu().numpy()
+    err = mlr_u_check(got, Uo, y[rows], TOL_BF16, factor_tol=1e-3, label_tol=1e-2)
+    print("large csr: masked U err", err, flush=True)
