@@ -11,6 +11,7 @@ struct DeviceInfo {
     int cus = 0;                                   // compute units
     int xcds = 0;                                  // accelerator dies, one L2 each (workgroup ids go round-robin over them)
     bool gemm_bf16_lds_set[3] = {false, false, false};   // dynamic-LDS attribute of sf_gemm_kernel<mode> set on this device
+    bool gemm_f32_lds_set[12] = {};                      // the same for the pipelined fp32 kernels (operand combination x tile shape)
     int softmax_wait_polls = 1000;                 // bound of the one-read softmax's wait for a partner's word
 };
 
@@ -43,6 +44,7 @@ struct GemmF32Args {
     const float* L_ptr;  // EPI_SHRINK: device scalar
     float lambda;        // EPI_SHRINK
     float* partial;      // scratch of gemm_f32_partial_bytes(M, N, K) for the k-split, or null (no split)
+    DeviceInfo* dev;     // the context's device facts; null: the plain kernel only
 };
 hipError_t launch_gemm_f32(const GemmF32Args& a, hipStream_t stream);
 // Scratch a contraction of this shape can use to split its k range over several

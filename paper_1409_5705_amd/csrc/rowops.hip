@@ -487,51 +487,110 @@ __global__ __launch_bounds__(256) void prox_rows_kernel(float* __restrict__ W, i
 }
 
 // ---------------------------------------------------------------------------
-// Power iteration on W^T W (three kernels per iteration).
+// Power iteration on W^T W: two kernels per iteration, W read from memory once.
 // ---------------------------------------------------------------------------
-// c[j] = sum_d W[j][d] b[d]; one wavefront per row.
-__global__ __launch_bounds__(256) void gemv_rows_kernel(const float* __restrict__ W, const float* __restrict__ b,
-                                                        float* __restrict__ c, int64_t J, int64_t D)
+// One workgroup per chunk of `rows` rows of W.  With b = g / ||g|| (g the raw vector of the previous iteration;
+// every workgroup takes the norm itself while it reads g anyway):
+//   c_j = W_j . b  for its rows (one wavefront per row at a time), then
+//   part[chunk][d] = sum over its rows of W[j][d] c_j   (the rows come from the cache the second time).
+constexpr int POWER_MAX_ROWS = 1024;
+__global__ __launch_bounds__(256) void power_step_kernel(const float* __restrict__ W, const float* __restrict__ g,
+                                                         float* __restrict__ part, int64_t J, int64_t D, int rows)
 {
-    const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (j >= J) return;
-    const int lane = threadIdx.x & 63;
-    float s = 0.f;
-    for (int64_t d = lane; d < D; d += 64) s += W[j * D + d] * b[d];
-    s = wave_sum(s);
-    if (lane == 0) c[j] = s;
+    __shared__ float sm[16];
+    __shared__ float c[POWER_MAX_ROWS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float nn = 0.f;
+    for (int64_t d = tid; d < D; d += 256) nn += g[d] * g[d];
+    const float inv = 1.0f / sqrtf(block_sum<256>(nn, sm));
+    const int64_t j0 = (int64_t)blockIdx.x * rows;
+    for (int r = wave; r < rows; r += 4) {
+        const int64_t j = j0 + r;
+        float s = 0.f;
+        if (j < J)
+            for (int64_t d = lane; d < D; d += 64) s += W[j * D + d] * g[d];
+        s = wave_sum(s);
+        if (lane == 0) c[r] = s * inv;
+    }
+    __syncthreads();
+    const int64_t j1 = j0 + rows < J ? j0 + rows : J;
+    for (int64_t d = tid; d < D; d += 256) {
+        float s = 0.f;
+        for (int64_t j = j0; j < j1; ++j) s += W[j * D + d] * c[j - j0];
+        part[(int64_t)blockIdx.x * D + d] = s;
+    }
 }
-// part[chunk][d] = sum over the chunk's rows of W[j][d] c[j].
-__global__ __launch_bounds__(256) void gemv_cols_partial_kernel(const float* __restrict__ W,
-                                                                const float* __restrict__ c,
-                                                                float* __restrict__ part, int64_t J, int64_t D,
-                                                                int64_t rows_per_chunk)
+// The same for rows of at most 1024 floats, 16-byte aligned (D % 4 == 0): a workgroup keeps its 16 rows in
+// registers (thread t holds columns 4 t .. 4 t + 3 of every row: one 16-byte load per row, all in flight
+// together), so W is read once and nothing waits on a chain of dependent loads.
+__global__ __launch_bounds__(256) void power_step16_kernel(const float* __restrict__ W, const float* __restrict__ g,
+                                                           float* __restrict__ part, int64_t J, int64_t D)
 {
-    const int64_t d = (int64_t)blockIdx.y * 256 + threadIdx.x;
-    if (d >= D) return;
-    const int64_t j0 = (int64_t)blockIdx.x * rows_per_chunk;
-    const int64_t j1 = j0 + rows_per_chunk < J ? j0 + rows_per_chunk : J;
-    float s = 0.f;
-    for (int64_t j = j0; j < j1; ++j) s += W[j * D + d] * c[j];
-    part[(int64_t)blockIdx.x * D + d] = s;
+    __shared__ float sm[16];
+    __shared__ float cw[16][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t d0 = 4 * (int64_t)tid, j0 = (int64_t)blockIdx.x * 16;
+    const bool have = d0 < D;
+    floatx4 w[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        w[r] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (have && j0 + r < J) w[r] = *reinterpret_cast<const floatx4*>(W + (j0 + r) * D + d0);
+    }
+    floatx4 g4 = {0.f, 0.f, 0.f, 0.f};
+    if (have) g4 = *reinterpret_cast<const floatx4*>(g + d0);
+    const float inv = 1.0f / sqrtf(block_sum<256>(g4[0] * g4[0] + g4[1] * g4[1] + g4[2] * g4[2] + g4[3] * g4[3], sm));
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float s = wave_sum(w[r][0] * g4[0] + w[r][1] * g4[1] + w[r][2] * g4[2] + w[r][3] * g4[3]);
+        if (lane == 0) cw[r][wave] = s;
+    }
+    __syncthreads();
+    floatx4 out = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float c = (((cw[r][0] + cw[r][1]) + cw[r][2]) + cw[r][3]) * inv;
+        out += w[r] * c;
+    }
+    if (have) *reinterpret_cast<floatx4*>(part + (int64_t)blockIdx.x * D + d0) = out;
 }
-// g = sum of partials (fixed order); L = ||g||; b = g / L.  One workgroup.
-__global__ __launch_bounds__(1024) void power_finish_kernel(const float* __restrict__ part, float* __restrict__ g,
-                                                            float* __restrict__ b, float* __restrict__ L_out,
-                                                            int64_t D, int64_t chunks)
+// g[d] = sum of the chunks' partials in a fixed order: 16 columns a workgroup, 16 interleaved groups of chunks
+// per column (eight loads in flight per thread), combined in order.
+__global__ __launch_bounds__(256) void power_reduce_kernel(const float* __restrict__ part, float* __restrict__ g,
+                                                           int64_t D, int64_t chunks)
+{
+    __shared__ float sm[16][17];
+    const int col = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int64_t d = (int64_t)blockIdx.x * 16 + col;
+    float s = 0.f;
+    if (d < D) {
+        int64_t ch = grp;
+        for (; ch + 7 * 16 < chunks; ch += 8 * 16) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = part[(ch + 16 * u) * D + d];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; ch < chunks; ch += 16) s += part[ch * D + d];
+    }
+    sm[grp][col] = s;
+    __syncthreads();
+    if (grp == 0 && d < D) {
+        float t = sm[0][col];
+#pragma unroll
+        for (int k = 1; k < 16; ++k) t += sm[k][col];
+        g[d] = t;
+    }
+}
+// L = ||g||.  One workgroup.
+__global__ __launch_bounds__(1024) void vec_norm_kernel(const float* __restrict__ g, float* __restrict__ L_out, int64_t D)
 {
     __shared__ float sm[16];
     float nn = 0.f;
-    for (int64_t d = threadIdx.x; d < D; d += 1024) {
-        float s = 0.f;
-        for (int64_t ch = 0; ch < chunks; ++ch) s += part[ch * D + d];
-        g[d] = s;
-        nn += s * s;
-    }
+    for (int64_t d = threadIdx.x; d < D; d += 1024) nn += g[d] * g[d];
     nn = block_sum<1024>(nn, sm);
-    const float L = sqrtf(nn);
-    if (threadIdx.x == 0) L_out[0] = L;
-    for (int64_t d = threadIdx.x; d < D; d += 1024) b[d] = g[d] / L;
+    if (threadIdx.x == 0) L_out[0] = sqrtf(nn);
 }
 
 unsigned grid_for(int64_t n)
@@ -655,35 +714,45 @@ hipError_t launch_prox_rows(float* W, int64_t J, int64_t D, int mode, hipStream_
     return hipGetLastError();
 }
 
+// Rows of W per workgroup of the power iteration: 16, more where that would be over 1024 workgroups.
+static int power_rows(int64_t J)
+{
+    int64_t r = (J + 1023) / 1024;
+    if (r < 16) r = 16;
+    return (int)r;
+}
+
 int64_t power_chunks(int64_t J)
 {
-    int64_t ch = (J + 63) / 64;
-    if (ch > 1024) ch = 1024;
-    if (ch < 1) ch = 1;
-    return ch;
+    const int64_t ch = (J + power_rows(J) - 1) / power_rows(J);
+    return ch < 1 ? 1 : ch;
 }
 
 hipError_t launch_power_iteration(const float* W, int64_t J, int64_t D, int iters, float* scratch, float* L_out,
                                   hipStream_t stream)
 {
+    const int rows = power_rows(J);
+    if (rows > POWER_MAX_ROWS) return hipErrorInvalidValue;
     const int64_t chunks = power_chunks(J);
-    const int64_t rows_per_chunk = (J + chunks - 1) / chunks;
-    float* b = scratch;
-    float* c = b + D;
-    float* part = c + J;
+    float* b = scratch;                     // the start vector, then unused
+    float* part = b + D + J;
     float* g = part + chunks * D;
     const float b0 = 1.0f / sqrtf((float)D);
     hipError_t e = launch_fill_u32(b, __builtin_bit_cast(uint32_t, b0), D, stream);
     if (e != hipSuccess) return e;
+    const bool in_registers = rows == 16 && D <= 1024 && D % 4 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0 &&
+                              reinterpret_cast<uintptr_t>(scratch) % 16 == 0 && J % 4 == 0;
     for (int it = 0; it < iters; ++it) {
-        hipLaunchKernelGGL(gemv_rows_kernel, dim3((unsigned)((J + 3) / 4)), dim3(256), 0, stream, W, b, c, J, D);
-        hipLaunchKernelGGL(gemv_cols_partial_kernel, dim3((unsigned)chunks, (unsigned)((D + 255) / 256)), dim3(256),
-                           0, stream, W, c, part, J, D, rows_per_chunk);
-        hipLaunchKernelGGL(power_finish_kernel, dim3(1), dim3(1024), 0, stream, part, g, b, L_out, D, chunks);
+        if (in_registers)
+            hipLaunchKernelGGL(power_step16_kernel, dim3((unsigned)chunks), dim3(256), 0, stream, W, it == 0 ? b : g, part, J, D);
+        else
+            hipLaunchKernelGGL(power_step_kernel, dim3((unsigned)chunks), dim3(256), 0, stream, W, it == 0 ? b : g, part, J, D, rows);
+        hipLaunchKernelGGL(power_reduce_kernel, dim3((unsigned)((D + 15) / 16)), dim3(256), 0, stream, part, g, D, chunks);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    return hipSuccess;
+    hipLaunchKernelGGL(vec_norm_kernel, dim3(1), dim3(1024), 0, stream, g, L_out, D);
+    return hipGetLastError();
 }
 
 }  // namespace sfb

@@ -424,6 +424,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
         const int64_t esz = batch->in_dtype == SFB_BF16 ? 2 : 4;
         if (batch->in_dtype == SFB_F32) {
             sfb::GemmF32Args g = {};
+            g.dev = &ctx->dev;
             g.A = static_cast<const float*>(batch->X); g.lda = D; g.a_kstrided = false;
             g.B = W; g.ldb = D; g.b_kstrided = false;
             g.C = Z; g.ldc = J;
@@ -456,6 +457,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
         SFB_RUN(KID_DIFF, sfb::launch_diff(static_cast<const float*>(batch->X), static_cast<const float*>(batch->Y), Vd,
                                            B * D, st));
         sfb::GemmF32Args g = {};
+        g.dev = &ctx->dev;
         g.A = Vd; g.lda = D; g.a_kstrided = false;
         g.B = W; g.ldb = D; g.b_kstrided = false;
         g.C = Q; g.ldc = J;
@@ -485,6 +487,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
             SFB_RUN(KID_COPY, hipMemcpyAsync(R, X, (size_t)(B * D * 4), hipMemcpyDeviceToDevice, st));
         } else {
             sfb::GemmF32Args g = {};  // R = X - A W   (contraction over the basis index j)
+            g.dev = &ctx->dev;
             g.A = A; g.lda = J; g.a_kstrided = false;
             g.B = W; g.ldb = D; g.b_kstrided = true;
             g.C = R; g.ldc = D;
@@ -496,6 +499,7 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
         }
         if (it == batch->ista_iters) break;
         sfb::GemmF32Args g = {};  // A = soft(A + (R W^T)/L, lambda/L)
+        g.dev = &ctx->dev;
         g.A = R; g.lda = D; g.a_kstrided = false;
         g.B = W; g.ldb = D; g.b_kstrided = false;
         g.C = A; g.ldc = J;
@@ -529,6 +533,7 @@ static int apply_impl(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* 
             Vf = Vs;
         }
         sfb::GemmF32Args g = {};  // both factors are strided along the SF index
+        g.dev = &ctx->dev;
         g.A = static_cast<const float*>(U); g.lda = J; g.a_kstrided = true;
         g.B = Vf; g.ldb = D; g.b_kstrided = true;
         g.C = W; g.ldc = D;
@@ -713,6 +718,7 @@ int sfb_mlr_sf_csr(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const sfb
             SFB_RUN(KID_FILL, sfb::launch_fill_u32(Xd, 0u, B * D, st));
             SFB_RUN(KID_CSR, sfb::launch_csr_scatter(X->indptr, X->indices, X->values, false, nullptr, Xd, B, D, X->nnz, D, 1, st));
             sfb::GemmF32Args g = {};
+            g.dev = &ctx->dev;
             g.A = Xd; g.lda = D; g.a_kstrided = false;
             g.B = W; g.ldb = D; g.b_kstrided = false;
             g.C = Z; g.ldc = J;
@@ -776,6 +782,7 @@ int sfb_apply_csr(sfb_ctx* ctx, float* W, int64_t J, int64_t D, const void* U, c
         SFB_RUN(KID_FILL, sfb::launch_fill_u32(Vd, 0u, N * D, st));
         SFB_RUN(KID_CSR, sfb::launch_csr_scatter(V->indptr, V->indices, V->values, false, coef, Vd, N, D, V->nnz, D, 1, st));
         sfb::GemmF32Args g = {};
+        g.dev = &ctx->dev;
         g.A = static_cast<const float*>(U); g.lda = J; g.a_kstrided = true;
         g.B = Vd; g.ldb = D; g.b_kstrided = true;
         g.C = W; g.ldc = D;
@@ -817,6 +824,7 @@ int sfb_sdca_mlr_sf(sfb_ctx* ctx, const float* W, int64_t J, int64_t D, const fl
     SFB_TRY(hipSetDevice(ctx->device));
     float* Zl = reinterpret_cast<float*>(ctx->ws);
     sfb::GemmF32Args g = {};
+    g.dev = &ctx->dev;
     g.A = X; g.lda = D; g.a_kstrided = false;
     g.B = W; g.ldb = D; g.b_kstrided = false;
     g.C = Zl; g.ldc = J;
