@@ -59,23 +59,3 @@ class SspSimulation:
         self.trace.append(("deliver", p, q, t))
         self._apply_ready(p)
         return True
-
-    def run(self, attempts):
-        for a in attempts:
-            if a[0] == "compute":
-                self.compute(a[1])
-            else:
-                self.deliver(a[1], a[2])
-
-    def drain(self):
-        """Deliver and apply everything, let every worker reach T sets."""
-        progress = True
-        while progress:
-            progress = False
-            for p in range(self.P):
-                for q in range(self.P):
-                    if q != p:
-                        while self.deliver(p, q):
-                            progress = True
-                if self.compute(p):
-                    progress = True

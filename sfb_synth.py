@@ -171,3 +171,29 @@ def ssp_attempts(P, n, seed):
             q = int(g.integers(P - 1))
             out.append(("deliver", p, q if q < p else q + 1))
     return out
+
+
+def ssp_replay(sim, attempts):
+    """Feeds a schedule of attempts (ssp_attempts) to a simulation object with compute(p) / deliver(p, q)
+    methods.  A schedule is an input like the batches: the same one goes to the oracle and to the product's
+    simulation; whether an attempt takes effect is decided by the object, not here."""
+    for a in attempts:
+        if a[0] == "compute":
+            sim.compute(a[1])
+        else:
+            sim.deliver(a[1], a[2])
+
+
+def ssp_drain(sim, P):
+    """The closing schedule: round after round, every worker is offered every peer's pending sets and one more
+    computation, until nothing takes effect any more."""
+    progress = True
+    while progress:
+        progress = False
+        for p in range(P):
+            for q in range(P):
+                if q != p:
+                    while sim.deliver(p, q):
+                        progress = True
+            if sim.compute(p):
+                progress = True

@@ -43,8 +43,8 @@ def test_replica_trajectories(ctx, sfb, oracle, P, s):
 
     sim = SspSimulation(ctx, P, s, torch.from_numpy(W0).to("cuda:0"), eta, lambda p, t: dev_batches[(p, t)], T)
     ora = ossp.SspOracle(P, s, W0, eta, lambda p, t: batches[(p, t)], T)
-    sim.run(attempts)
-    ora.run(attempts)
+    S.ssp_replay(sim, attempts)
+    S.ssp_replay(ora, attempts)
     torch.cuda.synchronize()
     assert sim.trace == ora.trace                      # same events took effect, same order of application
     if s >= 0:
@@ -57,8 +57,8 @@ def test_replica_trajectories(ctx, sfb, oracle, P, s):
         err = np.max(np.abs(mid[p].astype(np.float64) - ora.W[p]))
         assert err <= _bound(ora.W[p], W0, n_upd, TOL_F32), (p, err)
     # replicas differ while SF sets are in flight (unless BSP has just completed a round)
-    sim.drain()
-    ora.drain()
+    S.ssp_drain(sim, P)
+    S.ssp_drain(ora, P)
     torch.cuda.synchronize()
     assert sim.trace == ora.trace
     assert not sim.sets                                 # every SF set was applied by every peer and dropped

@@ -75,7 +75,7 @@ def test_counters_match_oracle_bookkeeping(sfb, oracle, P, s, seed):
     attempts = S.ssp_attempts(P, 1500, seed)
     clk, trace = drive_library(sfb, P, s, T, attempts)
     co = CountingOracle(ossp, P, s, T)
-    co.o.run(attempts)
+    S.ssp_replay(co.o, attempts)
     assert trace == co.o.trace
     assert clk.sfb_ssp_max_staleness_seen() == co.o.max_stale
     for p in range(P):
@@ -126,7 +126,7 @@ def test_oracle_bookkeeping_obeys_the_papers_conditions(oracle, P, s, seed):
         for q in range(P):
             ts = [e[3] for e in o.trace if e[0] == "apply" and e[1] == p and e[2] == q]
             assert ts == list(range(len(ts)))
-    o.drain()
+    S.ssp_drain(o, P)
     assert all(t == T for t in o.t)
     assert all(o.tau[p][q] == T for p in range(P) for q in range(P) if q != p)
 
