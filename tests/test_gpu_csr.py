@@ -212,3 +212,49 @@ def test_csr_edge_cases_and_check(ctx, sfb):
         ctx.sfb_apply_csr(Wb, torch.zeros((1, 12), dtype=torch.bfloat16, device="cuda:0"), i64([0, 1]), i32([3]),
                           f32([1]).to(torch.bfloat16), 1.0)
     assert e.value.code == sfb.SFB_EINVAL
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_gather_route_edge_cases(ctx, sfb, oracle, bf16):
+    """The route over the stored entries on inputs its re-laying has to survive: rows without entries, entries
+    outside the matrix (ignored), unsorted columns within a row (the stored entries still sum up), and no stored
+    entry at all."""
+    J, D, B = 72, 136, 5
+    W0 = S.normal_matrix(J, D, 0.2, seed=12)
+    if bf16:
+        W0 = S.round_to_bf16(W0)
+    g = np.random.default_rng(7)
+    # row 0: unsorted columns; row 1: empty; row 2: one entry out of range on either side; row 3: last column; row 4: first
+    rows = [[(100, 0.5), (3, -1.0), (64, 2.0)], [], [(-1, 9.0), (7, 1.5), (D, 9.0)], [(D - 1, -0.25)], [(0, 1.0)]]
+    indptr = np.zeros(B + 1, np.int64)
+    idx, val = [], []
+    for i, r in enumerate(rows):
+        for c, v in r:
+            idx.append(c); val.append(v)
+        indptr[i + 1] = len(idx)
+    idx = np.array(idx, np.int32); val = np.array(val, np.float32)
+    y = g.integers(0, J, B).astype(np.int32)
+    keep = (idx >= 0) & (idx < D)
+    Xd = np.zeros((B, D), np.float32)
+    for i in range(B):
+        for t in range(indptr[i], indptr[i + 1]):
+            if keep[t]:
+                Xd[i, idx[t]] += val[t]
+    Uo, _ = oracle.mlr_sf(W0, Xd, y)
+    dt = torch.bfloat16 if bf16 else torch.float32
+    vals = dev(S.bf16_bits(val)).view(torch.bfloat16) if bf16 else dev(val)
+    U = torch.empty((B, J), dtype=dt, device="cuda:0")
+    ctx.sfb_set_csr_route(2)
+    try:
+        ctx.sfb_mlr_sf_csr(dev(W0), dev(indptr), dev(idx), vals, dev(y), U)
+        assert rel_err(host(U), Uo) <= (TOL_BF16 if bf16 else TOL_F32)
+        mlr_u_check(host(U), Uo, y, TOL_BF16 if bf16 else TOL_F32, label_tol=1e-2 if bf16 else None)
+        # nothing stored: every logit is zero, every probability 1/J
+        U2 = torch.empty_like(U)
+        empty_i = torch.zeros((0,), dtype=torch.int32, device="cuda:0")
+        empty_v = torch.zeros((0,), dtype=dt, device="cuda:0")
+        ctx.sfb_mlr_sf_csr(dev(W0), dev(np.zeros(B + 1, np.int64)), empty_i, empty_v, dev(y), U2)
+        want = np.full((B, J), 1.0 / J); want[np.arange(B), y] -= 1.0
+        assert rel_err(host(U2), want) <= (TOL_BF16 if bf16 else TOL_F32)
+    finally:
+        ctx.sfb_set_csr_route(0)
