@@ -2,8 +2,11 @@
 // roofline fractions are quoted against: the MFMA pipes (a register-only loop of
 // bf16 32x32x16 and fp32 32x32x2 MFMAs, one and two wavefronts per SIMD) and HBM
 // (streaming read, copy and read-modify-write of buffers far larger than the
-// caches, 16 bytes per lane).  Prints one JSON object.  Used by `bench.py --peaks`;
-// not part of the library.
+// caches, 16 bytes per lane), and what ONE compute unit can pull through its
+// vector-memory path when a quarter of the CUs stream alone (one workgroup each:
+// lines that miss every cache against lines that stay in the L2, 4 and 16
+// wavefronts, 8 and 16 bytes per lane).  Prints one JSON object.  Used by
+// `bench.py --peaks`; not part of the library.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -80,6 +83,38 @@ __global__ __launch_bounds__(256) void stream_kernel(const floatx4* __restrict__
     if (MODE == 0) sink[(size_t)blockIdx.x * 256 + threadIdx.x] = acc[0] + acc[1] + acc[2] + acc[3];
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// One workgroup of T threads reads its own contiguous region of `footprint` bytes `passes` times, 16 accesses
+// of W bytes per lane in flight.  footprint and the region are multiples of 16 * T * W.
+template <int W, int T>
+__global__ __launch_bounds__(T) void cu_read_kernel(const char* __restrict__ p, uint32_t* __restrict__ sink, size_t region,
+                                                    uint32_t footprint, int passes)
+{
+    const char* base = p + (size_t)blockIdx.x * region;
+    const auto rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, footprint, 0x00020000);
+    const uint32_t lane_off = threadIdx.x * W, step = T * W;
+    uint32_t acc = 0;
+    for (int ps = 0; ps < passes; ++ps)
+        for (uint32_t soff = 0; soff < footprint; soff += 16 * step) {
+            if (W == 16) {
+                u32x4 v[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, soff + i * step, 0);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc += v[i][0] ^ v[i][1] ^ v[i][2] ^ v[i][3];
+            } else {
+                u32x2 v[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) v[i] = __builtin_amdgcn_raw_buffer_load_b64(rs, lane_off, soff + i * step, 0);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc += v[i][0] ^ v[i][1];
+            }
+        }
+    if (acc == 0x12345678u) sink[threadIdx.x] = acc;   // never true for a zeroed buffer: keeps the loads alive
+}
+
 template <typename F>
 int time_ms(F launch, int reps, float* ms_out)
 {
@@ -144,6 +179,29 @@ int main()
         if (time_ms([&] { hipLaunchKernelGGL(stream_kernel<2>, dim3(grid), dim3(256), 0, 0, a, a, n4, sink); }, 5, &ms)) return 1;
         if (2.0 * bytes / (ms * 1e-3) / 1e9 > gbs[2]) gbs[2] = 2.0 * bytes / (ms * 1e-3) / 1e9;
     }
+    // One CU's read rate: a quarter of the CUs, one workgroup each, so that neither HBM nor an L2 is the limit.
+    // "miss": 32 MiB per workgroup read once; "l2": 256 KiB per workgroup read 128 times.
+    double cu[6];
+    {
+        const int wgs = cus / 4;
+        const size_t region = (size_t)32 << 20;
+        const char* pa = reinterpret_cast<const char*>(a);
+        uint32_t* sk = reinterpret_cast<uint32_t*>(sink);
+        const uint32_t big = (uint32_t)region, small = 256u << 10;
+        int c = 0;
+        if (time_ms([&] { hipLaunchKernelGGL((cu_read_kernel<16, 256>), dim3(wgs), dim3(256), 0, 0, pa, sk, region, big, 1); }, 3, &ms)) return 1;
+        cu[c++] = (double)big / (ms * 1e-3) / 1e9;
+        if (time_ms([&] { hipLaunchKernelGGL((cu_read_kernel<16, 1024>), dim3(wgs), dim3(1024), 0, 0, pa, sk, region, big, 1); }, 3, &ms)) return 1;
+        cu[c++] = (double)big / (ms * 1e-3) / 1e9;
+        if (time_ms([&] { hipLaunchKernelGGL((cu_read_kernel<16, 256>), dim3(wgs), dim3(256), 0, 0, pa, sk, region, small, 128); }, 3, &ms)) return 1;
+        cu[c++] = 128.0 * small / (ms * 1e-3) / 1e9;
+        if (time_ms([&] { hipLaunchKernelGGL((cu_read_kernel<16, 1024>), dim3(wgs), dim3(1024), 0, 0, pa, sk, region, small, 128); }, 3, &ms)) return 1;
+        cu[c++] = 128.0 * small / (ms * 1e-3) / 1e9;
+        if (time_ms([&] { hipLaunchKernelGGL((cu_read_kernel<8, 256>), dim3(wgs), dim3(256), 0, 0, pa, sk, region, small, 128); }, 3, &ms)) return 1;
+        cu[c++] = 128.0 * small / (ms * 1e-3) / 1e9;
+        if (time_ms([&] { hipLaunchKernelGGL((cu_read_kernel<8, 1024>), dim3(wgs), dim3(1024), 0, 0, pa, sk, region, small, 128); }, 3, &ms)) return 1;
+        cu[c++] = 128.0 * small / (ms * 1e-3) / 1e9;
+    }
     CK(hipFree(a));
     CK(hipFree(b));
     CK(hipFree(sink));
@@ -151,7 +209,10 @@ int main()
            "\"mfma_bf16_tflops\": {\"one_wave_per_simd\": %.1f, \"two_waves_per_simd\": %.1f}, "
            "\"mfma_f32_tflops\": {\"one_wave_per_simd\": %.1f, \"two_waves_per_simd\": %.1f}, "
            "\"hbm_gbs\": {\"read\": %.0f, \"copy_read_plus_write\": %.0f, \"read_modify_write\": %.0f}, "
+           "\"one_cu_read_gbs\": {\"miss_4_waves\": %.1f, \"miss_16_waves\": %.1f, \"l2_4_waves\": %.1f, \"l2_16_waves\": %.1f, "
+           "\"l2_4_waves_8_byte\": %.1f, \"l2_16_waves_8_byte\": %.1f}, "
            "\"buffer_gib\": 4}\n",
-           prop.gcnArchName, cus, prop.clockRate / 1000, tf[0], tf[1], tf[2], tf[3], gbs[0], gbs[1], gbs[2]);
+           prop.gcnArchName, cus, prop.clockRate / 1000, tf[0], tf[1], tf[2], tf[3], gbs[0], gbs[1], gbs[2], cu[0], cu[1], cu[2],
+           cu[3], cu[4], cu[5]);
     return 0;
 }

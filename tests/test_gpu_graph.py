@@ -135,3 +135,40 @@ def test_mlr_bf16_step_on_split_storage_replays_from_a_graph(sfb):
         junk = torch.randn(1 << 20, device="cuda:0").sum().item()
         assert np.isfinite(junk)
     ctx.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_apply_static_replays_from_a_graph(sfb, dtype):
+    """sfb_apply_static is the entry point for callers that cannot allocate: captured on its own (the context never
+    gets a workspace), replayed with eager work in between, it must give the bits of eager sfb_apply."""
+    J, D, N = (1000, 520, 130) if dtype == "bf16" else (264, 200, 96)
+    W0 = dev(S.normal_matrix(J, D, 0.02, seed=4))
+    Uh, Vh = S.mlr_peer_sf(J, D, N, seed=4, step=0, peer=0, bf16=(dtype == "bf16"))
+    if dtype == "bf16":
+        U, V = dev(S.bf16_bits(Uh)).view(torch.bfloat16), dev(S.bf16_bits(Vh)).view(torch.bfloat16)
+    else:
+        U, V = dev(Uh.astype(np.float32)), dev(Vh.astype(np.float32))
+    ref_ctx = sfb.Context(0)
+    Wr = W0.clone()
+    ref = []
+    for _ in range(3):
+        ref_ctx.sfb_apply(Wr, U, V, 0.05)
+        torch.cuda.synchronize()
+        ref.append(Wr.clone())
+    ref_ctx.close()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx = sfb.Context(0)                        # no workspace is ever set on this context
+        W = W0.clone()
+        ctx.sfb_apply_static(W0.clone(), U, V, 0.05)     # one eager call first (kernel attributes are set on first use)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            ctx.sfb_apply_static(W, U, V, 0.05)
+    for k in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(W, ref[k]), "replay %d differs from eager sfb_apply" % k
+        junk = torch.randn(1 << 20, device="cuda:0").sum().item()
+        assert np.isfinite(junk)
+    ctx.close()
