@@ -84,3 +84,19 @@ def mlr_u_check(got, ref, y, tol, factor_tol=None, label_tol=None):
     factor = np.sum(gm * rm, axis=1)[ok] / den_f[ok]
     assert np.all(np.abs(factor - 1.0) < factor_tol), (float(factor.min()), float(factor.max()))
     return err
+
+
+def dml_follow_kink(oracle, Uo, n_active, U_got, W, X, Y, sim, margin, width):
+    """A dissimilar pair whose squared distance is within `width` of the margin may fall on either side of the
+    hinge's kink in fp32: both decisions are valid.  For those pairs the oracle's row follows the decision the
+    library took (its active row, from an oracle call with the margin moved out of the way, or zero), so that
+    everything else stays comparable element by element.  Returns (Uo, n_active, number of such pairs)."""
+    d = np.sum(((np.asarray(X, dtype=np.float64) - Y) @ np.asarray(W, dtype=np.float64).T) ** 2, axis=1)
+    near = np.flatnonzero((np.asarray(sim) < 0) & (np.abs(d - margin) < width))
+    if near.size:
+        U_on, _, _ = oracle.dml_sf(W, X, Y, sim, margin=margin + 2.0 * width + 1.0)
+        for i in near:
+            took = bool(np.any(U_got[i] != 0))
+            n_active += int(took) - int(np.any(Uo[i] != 0))
+            Uo[i] = U_on[i] if took else 0.0
+    return Uo, n_active, int(near.size)

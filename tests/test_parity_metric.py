@@ -58,3 +58,38 @@ def test_mlr_u_check_catches_what_the_plain_metric_misses(oracle, J):
     bad[0, j] = U[0, j] * 3.0
     with pytest.raises(AssertionError):
         mlr_u_check(bad, U, y, TOL_BF16)
+
+
+def test_dml_follow_kink_only_touches_pairs_at_the_kink(oracle):
+    """Hand-built pairs: one dissimilar pair a hair below the margin, one clearly active, one clearly inactive.
+    Whatever the library decided for the first, the oracle's row follows it; a wrong decision on the others
+    stays a mismatch."""
+    from parity import dml_follow_kink
+    K = D = 4
+    W = np.eye(K, D)
+    X = np.zeros((3, D)); Y = np.zeros((3, D))
+    X[0, 0] = np.sqrt(1.0 - 2e-6)      # d = 1 - 2e-6
+    X[1, 1] = 0.5                      # d = 0.25
+    X[2, 2] = 2.0                      # d = 4
+    sim = np.array([-1, -1, -1], dtype=np.int8)
+    Uo, _, no = oracle.dml_sf(W, X, Y, sim, margin=1.0)
+    assert no == 2 and np.any(Uo[0] != 0)
+    # the library took the other side for pair 0, and (wrongly) switched pair 2 on
+    got = Uo.copy()
+    got[0] = 0.0
+    got[2] = -2.0 * X[2]
+    U2, n2, near = dml_follow_kink(oracle, Uo.copy(), no, got, W, X, Y, sim, 1.0, 1e-5)
+    assert near == 1 and n2 == 1
+    np.testing.assert_array_equal(U2[0], 0.0)
+    np.testing.assert_array_equal(U2[1], Uo[1])
+    np.testing.assert_array_equal(U2[2], 0.0)          # not at the kink: the oracle's own decision stands
+    assert rel_err(got, U2) > TOL_F32
+    # and back: the library active where the oracle (at d = 1 + 2e-6) is not
+    X[0, 0] = np.sqrt(1.0 + 2e-6)
+    Uo, _, no = oracle.dml_sf(W, X, Y, sim, margin=1.0)
+    assert no == 1 and not np.any(Uo[0] != 0)
+    got = Uo.copy()
+    got[0] = -2.0 * X[0]
+    U2, n2, near = dml_follow_kink(oracle, Uo.copy(), no, got, W, X, Y, sim, 1.0, 1e-5)
+    assert near == 1 and n2 == 2
+    np.testing.assert_allclose(U2[0], -2.0 * X[0], rtol=1e-15)
