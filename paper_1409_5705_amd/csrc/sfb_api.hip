@@ -244,8 +244,15 @@ int sfb_profile_enable(sfb_ctx* ctx, int on)
         if (!sp) return SFB_EINVAL;
         for (int i = 0; i < cap; ++i) {
             hipError_t e = hipEventCreate(&sp[i].t0);
-            if (e == hipSuccess) e = hipEventCreate(&sp[i].t1);
-            if (e != hipSuccess) {
+            if (e == hipSuccess) {
+                e = hipEventCreate(&sp[i].t1);
+                if (e != hipSuccess) (void)hipEventDestroy(sp[i].t0);
+            }
+            if (e != hipSuccess) {   // give back the pairs made so far
+                for (int k = 0; k < i; ++k) {
+                    (void)hipEventDestroy(sp[k].t0);
+                    (void)hipEventDestroy(sp[k].t1);
+                }
                 delete[] sp;
                 return hip_fail(ctx, e);
             }
