@@ -5,7 +5,7 @@
 // caches, 16 bytes per lane), and what ONE compute unit can pull through its
 // vector-memory path when a quarter of the CUs stream alone (one workgroup each:
 // lines that miss every cache against lines that stay in the L2, 4 and 16
-// wavefronts, 8 and 16 bytes per lane).  Prints one JSON object.  Used by
+// wavefronts, 8 and 16 bytes per lane; and the same for a stream of stores).  Prints one JSON object.  Used by
 // `bench.py --peaks`; not part of the library.
 #include <hip/hip_runtime.h>
 
@@ -115,6 +115,20 @@ __global__ __launch_bounds__(T) void cu_read_kernel(const char* __restrict__ p, 
     if (acc == 0x12345678u) sink[threadIdx.x] = acc;   // never true for a zeroed buffer: keeps the loads alive
 }
 
+// The same for stores: each workgroup fills its own region with 16-byte non-temporal stores, 16 per lane back to back.
+template <int T>
+__global__ __launch_bounds__(T) void cu_write_kernel(char* __restrict__ p, size_t region, uint32_t footprint)
+{
+    char* base = p + (size_t)blockIdx.x * region;
+    const auto rs = __builtin_amdgcn_make_buffer_rsrc(base, 0, footprint, 0x00020000);
+    const uint32_t lane_off = threadIdx.x * 16, step = T * 16;
+    const u32x4 v = {threadIdx.x, blockIdx.x, 0u, 0u};
+    for (uint32_t soff = 0; soff < footprint; soff += 16 * step) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) __builtin_amdgcn_raw_buffer_store_b128(v, rs, lane_off, soff + i * step, 2);
+    }
+}
+
 template <typename F>
 int time_ms(F launch, int reps, float* ms_out)
 {
@@ -202,6 +216,16 @@ int main()
         if (time_ms([&] { hipLaunchKernelGGL((cu_read_kernel<8, 1024>), dim3(wgs), dim3(1024), 0, 0, pa, sk, region, small, 128); }, 3, &ms)) return 1;
         cu[c++] = 128.0 * small / (ms * 1e-3) / 1e9;
     }
+    double cuw[2];
+    {
+        const int wgs = cus / 4;
+        const size_t region = (size_t)32 << 20;
+        char* pb = reinterpret_cast<char*>(b);
+        if (time_ms([&] { hipLaunchKernelGGL((cu_write_kernel<256>), dim3(wgs), dim3(256), 0, 0, pb, region, (uint32_t)region); }, 3, &ms)) return 1;
+        cuw[0] = (double)region / (ms * 1e-3) / 1e9;
+        if (time_ms([&] { hipLaunchKernelGGL((cu_write_kernel<1024>), dim3(wgs), dim3(1024), 0, 0, pb, region, (uint32_t)region); }, 3, &ms)) return 1;
+        cuw[1] = (double)region / (ms * 1e-3) / 1e9;
+    }
     CK(hipFree(a));
     CK(hipFree(b));
     CK(hipFree(sink));
@@ -211,8 +235,9 @@ int main()
            "\"hbm_gbs\": {\"read\": %.0f, \"copy_read_plus_write\": %.0f, \"read_modify_write\": %.0f}, "
            "\"one_cu_read_gbs\": {\"miss_4_waves\": %.1f, \"miss_16_waves\": %.1f, \"l2_4_waves\": %.1f, \"l2_16_waves\": %.1f, "
            "\"l2_4_waves_8_byte\": %.1f, \"l2_16_waves_8_byte\": %.1f}, "
+           "\"one_cu_write_gbs\": {\"4_waves\": %.1f, \"16_waves\": %.1f}, "
            "\"buffer_gib\": 4}\n",
            prop.gcnArchName, cus, prop.clockRate / 1000, tf[0], tf[1], tf[2], tf[3], gbs[0], gbs[1], gbs[2], cu[0], cu[1], cu[2],
-           cu[3], cu[4], cu[5]);
+           cu[3], cu[4], cu[5], cuw[0], cuw[1]);
     return 0;
 }
