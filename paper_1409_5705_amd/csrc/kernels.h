@@ -133,7 +133,8 @@ hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool ou
 // current device since the library was loaded (copies a device counter: the caller synchronises first).
 hipError_t softmax_fallbacks(unsigned long long* count);
 // V = X - Y (elementwise, n elements).
-hipError_t launch_diff(const float* X, const float* Y, float* V, int64_t n, hipStream_t stream);
+// V = X - Y over n floats; *counter (nullable, device) is set to 0 by the same launch.
+hipError_t launch_diff(const float* X, const float* Y, float* V, int64_t n, int32_t* counter, hipStream_t stream);
 // DML coefficient: d = ||Q_i||^2; c = +2 (sim>0), -2 (sim<=0 and d<margin), else 0; U_i = c Q_i.
 // n_active (nullable) must have been zeroed; it is incremented once per active row.
 hipError_t launch_dml_scale(const float* Q, const int8_t* sim, float* U, int32_t* n_active,

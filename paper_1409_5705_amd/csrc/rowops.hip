@@ -330,9 +330,11 @@ __global__ __launch_bounds__(1024) void mlr_softmax_cluster_kernel(const float* 
     }
 }
 
+// V = X - Y; also clears *counter (nullable): the count of active pairs a later kernel of the same call adds to.
 __global__ __launch_bounds__(256) void diff_kernel(const float* __restrict__ X, const float* __restrict__ Y,
-                                                   float* __restrict__ V, int64_t n)
+                                                   float* __restrict__ V, int64_t n, int32_t* __restrict__ counter)
 {
+    if (counter && blockIdx.x == 0 && threadIdx.x == 0) *counter = 0;
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) V[i] = X[i] - Y[i];
 }
@@ -660,10 +662,10 @@ hipError_t launch_mlr_softmax(const float* Z, const int32_t* y, void* U, bool ou
     return hipGetLastError();
 }
 
-hipError_t launch_diff(const float* X, const float* Y, float* V, int64_t n, hipStream_t stream)
+hipError_t launch_diff(const float* X, const float* Y, float* V, int64_t n, int32_t* counter, hipStream_t stream)
 {
-    if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(diff_kernel, dim3(grid_for(n)), dim3(256), 0, stream, X, Y, V, n);
+    if (n <= 0) return counter ? launch_fill_u32(counter, 0u, 1, stream) : hipSuccess;
+    hipLaunchKernelGGL(diff_kernel, dim3(grid_for(n)), dim3(256), 0, stream, X, Y, V, n, counter);
     return hipGetLastError();
 }
 

@@ -461,8 +461,9 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
         if (!batch->Y || !batch->sim || !V || !aligned16(batch->Y)) return SFB_EINVAL;
         float* Q = reinterpret_cast<float*>(ctx->ws);
         float* Vd = static_cast<float*>(V);
+        // (the same launch clears the count of active pairs that the scaling kernel below adds to)
         SFB_RUN(KID_DIFF, sfb::launch_diff(static_cast<const float*>(batch->X), static_cast<const float*>(batch->Y), Vd,
-                                           B * D, st));
+                                           B * D, n_active, st));
         sfb::GemmF32Args g = {};
         g.dev = &ctx->dev;
         g.A = Vd; g.lda = D; g.a_kstrided = false;
@@ -472,7 +473,6 @@ int sfb_compute_sf(sfb_ctx* ctx, int32_t model, const float* W, int64_t J, int64
         g.epilogue = sfb::EPI_STORE;
         if (sfb::gemm_f32_partial_bytes(B, J, D) > 0) g.partial = reinterpret_cast<float*>(ctx->ws + round_up(B * J * 4));
         SFB_RUN(KID_GEMM_F32_STORE, sfb::launch_gemm_f32(g, st));
-        if (n_active) SFB_RUN(KID_FILL, sfb::launch_fill_u32(n_active, 0u, 1, st));
         SFB_RUN(KID_DML_SCALE, sfb::launch_dml_scale(Q, batch->sim, static_cast<float*>(U), n_active, batch->margin, B, J, st));
         return SFB_OK;
     }
