@@ -288,6 +288,10 @@ def main():
     ap.add_argument("--zero-frac", type=float, default=None,
                     help="mlr_large_bf16: fraction of feature entries that are zero (default: the workload's 0.9); with "
                          "--csr, 0.995 is the tf-idf-like density at which sfb_mlr_sf_csr goes over the stored entries")
+    ap.add_argument("--peers", type=int, default=0,
+                    help="headline workload: also time sfb_apply on the local SF block plus this many peers' blocks "
+                         "(N = (peers + 1) * B rows in one call: one GPU's share of a broadcast step); reported as "
+                         "`apply_with_peers`, beside the headline, never as `value`")
     ap.add_argument("--csr", action="store_true",
                     help="mlr_large_bf16: hand the samples over as CSR rows (sfb_mlr_sf_csr / sfb_apply_csr)")
     args = ap.parse_args()
@@ -508,6 +512,51 @@ def main():
     }
     if args.measured_peaks is not None:
         out["measured_peaks"] = args.measured_peaks
+    if args.peers > 0 and not args.csr:
+        # One GPU's share of a broadcast step with P = peers + 1 workers (Section 3: every worker applies the SF sets
+        # of all workers): the local block and the peers' blocks in one sfb_apply call.  Peer factors by the input
+        # recipe of the peer workloads (softmax of N(0,1) logits minus a uniform one-hot; samples like X), drawn on
+        # the device because of their size.
+        P1 = args.peers + 1
+        g2 = torch.Generator(device=dev)
+        g2.manual_seed(1)
+        U_all = torch.empty((P1 * B, J), dtype=torch.bfloat16, device=dev)
+        V_all = torch.empty((P1 * B, D), dtype=torch.bfloat16, device=dev)
+        U_all[:B].copy_(U)
+        V_all[:B].copy_(Xs[0])
+        for q in range(1, P1):
+            for r0 in range(0, B, 128):          # (in pieces: an fp32 block of logits is 1.3 GB)
+                lg = torch.randn((128, J), dtype=torch.float32, device=dev, generator=g2)
+                pr = torch.softmax(lg, dim=1)
+                lab = torch.randint(0, J, (128,), device=dev, generator=g2)
+                pr[torch.arange(128, device=dev), lab] -= 1.0
+                U_all[q * B + r0:q * B + r0 + 128].copy_(pr)
+            xv = torch.randn((B, D), dtype=torch.float32, device=dev, generator=g2)
+            xv *= (torch.rand((B, D), device=dev, generator=g2) >= zero_frac)
+            V_all[q * B:(q + 1) * B].copy_(xv)
+        del lg, pr, xv
+        for _ in range(2):
+            ctx.sfb_apply(W, U_all, V_all, eta)
+        torch.cuda.synchronize()
+        ctx.sfb_profile_enable(True)
+        ctx.sfb_profile_collect()
+        reps = 3
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(ctx.stream)
+        for _ in range(reps):
+            ctx.sfb_apply(W, U_all, V_all, eta)
+        e1.record(ctx.stream)
+        torch.cuda.synchronize()
+        prof2 = ctx.sfb_profile_collect()
+        ctx.sfb_profile_enable(False)
+        k2 = {k: v[1] / v[0] for k, v in prof2.items()}
+        fl = 2.0 * P1 * B * J * D
+        out["apply_with_peers"] = {
+            "peers": args.peers, "N": P1 * B, "ms_per_call": e0.elapsed_time(e1) / reps,
+            "transposes_ms": k2.get("apply_bf16_transpose"), "apply_gemm_ms": k2.get("apply_bf16"),
+            "tflops": fl / k2["apply_bf16"] / 1e9, "mfma_frac": fl / k2["apply_bf16"] / 1e9 / PEAK_BF16_TFLOPS,
+            "updates_per_s_apply_only": P1 * B / (e0.elapsed_time(e1) / reps * 1e-3)}
+        del U_all, V_all
     if split and not args.no_other_layout:
         # the same steps with W kept as an fp32 array plus bf16 working copy (the library's other layout), untimed
         # set-up, a few timed steps: reported beside the headline, never as `value`

@@ -265,6 +265,33 @@ def test_apply_bf16(ctx, sfb, oracle, N, J, D):
     _trajectory_check(host(W), ref, W0, 1, TOL_F32)
 
 
+def test_apply_bf16_local_plus_seven_peer_blocks(ctx, sfb, oracle):
+    """One worker's share of a broadcast step with eight workers (Section 3: every worker applies the factor
+    sets of all workers): eight blocks of 1024 + a ragged 37 rows in one call (k = 8229, 129 slices) against the
+    oracle, and the same blocks applied one call each (the sum is the same up to the order of additions)."""
+    J, D, P = 520, 328, 8
+    blocks = [S.mlr_peer_sf(J, D, 1024 if q < P else 37, seed=5, step=0, peer=q, bf16=True) for q in range(P + 1)]
+    U = np.concatenate([b[0] for b in blocks]); V = np.concatenate([b[1] for b in blocks])
+    W0 = S.normal_matrix(J, D, 0.01, seed=5)
+    W = dev(W0)
+    ctx.sfb_apply(W, dev_bf16(U), dev_bf16(V), 0.001)
+    ref = oracle.apply(W0, U, V, 0.001)
+    _trajectory_check(host(W), ref, W0, 1, TOL_F32)
+    W2 = dev(W0)
+    for Ub, Vb in blocks:
+        ctx.sfb_apply(W2, dev_bf16(Ub), dev_bf16(Vb), 0.001)
+    _trajectory_check(host(W2), ref, W0, len(blocks), TOL_F32)
+    # on the two planes as well (the benchmark's layout)
+    c2 = sfb.Context(0)
+    W3 = dev(W0)
+    c2.sfb_split_attach(W3)
+    c2.sfb_apply(W3, dev_bf16(U), dev_bf16(V), 0.001)
+    c2.sfb_split_export(W3)
+    torch.cuda.synchronize()
+    assert torch.equal(W3, W)
+    c2.close()
+
+
 def test_bf16_shadow_stays_current(sfb, oracle):
     """With a bf16 working copy of W attached, SFs after several applies (and a prox) equal those of a
     context that converts W afresh on every call, bit for bit."""
