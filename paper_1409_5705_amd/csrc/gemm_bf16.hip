@@ -1,4 +1,4 @@
-// bf16 MFMA kernel (v_mfma_f32_32x32x16_bf16, fp32 accumulate) of the large
+// bf16 MFMA kernel (v_mfma_f32_16x16x32_bf16, fp32 accumulate) of the large
 // multiclass-logistic path on gfx950, and the small layout kernels around it:
 //
 //   forward:  Z[b][j]  = sum_d X[b][d] * bf16(W[j][d])          (logits W x, Figure 2 "predict")
@@ -16,31 +16,36 @@
 // What the measurements on MI355X dictated:
 //   * The vector-memory path of a CU sustains ~110 outstanding 128-byte requests
 //     and a wavefront issues at most one instruction every four cycles, so the
-//     kernel is bound by requests and instructions per flop, not by MFMA rate.
+//     kernel must be lean in requests and instructions per flop.
 //     Hence the largest tile the register file holds, 256 x 256 per workgroup of
 //     four wavefronts (one per SIMD, 128 x 128 = 256 accumulator registers
 //     each), aligned bf16 operands only (every request is a whole line), and
 //     operand tiles that go from global memory straight into LDS
 //     (global_load_lds_dwordx4: no staging registers, no LDS write
 //     instructions, 16 load instructions per wavefront and k-slice).
+//   * The matrix pipes run at the clock the chip grants, and that clock falls with
+//     the bits that toggle in them: on operands that change, the 16x16x32 form of
+//     the MFMA keeps a higher clock than the 32x32x16 form for the same fragment
+//     bytes from LDS (register-only loops: 1.86 against 1.72 PFLOP/s).  A wavefront's
+//     128 x 128 block is therefore 8 x 8 tiles of 16 x 16, 64 MFMAs per 32 of k.
 //   * LDS rows are 128 bytes, the eight 16-byte chunks of a row XOR-swizzled by
 //     a function of the row: conflict-free operand reads, no padding.  A direct
 //     load writes 64 lanes x 16 bytes = 8 consecutive LDS rows; the swizzle is
 //     applied on the global side (each lane fetches the chunk that belongs in
 //     its slot).
-//   * Two LDS stages of 64 KiB.  The loads of slice s+2 may start as soon as
-//     every wavefront has read the last fragments of slice s (middle of its
-//     third k-step) and must have landed when slice s+1 ends; they are spread
-//     over the two and a half k-steps in between, about one per three MFMAs
-//     (a burst of loads blocks the wavefront in the memory-issue stage while the
-//     MFMA pipe runs dry), and the last of them still has one and a half
-//     k-steps to land.  Fragments
-//     are double-buffered in registers across the barriers, so the MFMA pipe
+//   * Two LDS stages of 64 KiB, a slice being two k-steps of 32.  The loads of
+//     slice s+2 may start as soon as every wavefront has read the last fragments
+//     of slice s (after its first k-step: the second step's fragments are read
+//     under the first step's MFMAs) and must have landed three quarters into slice
+//     s+1; they are spread over the three quarters of a slice in between, about
+//     one per five MFMAs (a burst of loads blocks the wavefront in the
+//     memory-issue stage while the MFMA pipe runs dry).  Fragments are
+//     double-buffered in registers across the barriers, so the MFMA pipe
 //     does not drain at a slice boundary.  Two workgroup barriers per k-slice.
-//   * The loader permutes the rows of the B tile inside LDS so that the four
-//     MFMA tiles of a lane hold four consecutive columns of C: the epilogue
-//     reads and writes C with 16-byte accesses (512 contiguous bytes per
-//     half-wave) without any cross-lane shuffle.
+//   * The loader permutes the rows of the B tile inside LDS so that the eight
+//     MFMA tiles of a lane hold eight consecutive columns of C (forward: two
+//     groups of four): the epilogue reads and writes C and the 16-bit planes
+//     with 16-byte accesses that cover whole lines, without any cross-lane shuffle.
 //   * Workgroups are persistent (one per CU); ids are dealt round-robin to the
 //     XCDs (one L2 each; 8 of 32 CUs on MI355X, both read from the device): the
 //     workgroups of an XCD walk consecutive tiles of a raster in which tiles
@@ -56,13 +61,12 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int BK = 64;                   // k-slice: one 128-byte LDS row of bf16
 constexpr int BM = 256, BN = 256;        // workgroup tile
-constexpr int TM = 4, TN = 4;            // 32 x 32 MFMA tiles per wavefront (2 x 2 wavefronts)
+constexpr int TM = 8, TN = 8;            // 16 x 16 MFMA tiles per wavefront: 128 x 128 (2 x 2 wavefronts)
 constexpr int NT = 256;
 constexpr uint32_t STAGE = 0x10000u;     // bytes of one LDS stage: [A tile 32 KiB][B tile 32 KiB]
 constexpr uint32_t B_OFF = BM * 128;
@@ -72,19 +76,19 @@ constexpr int LDS_BYTES = 2 * STAGE;
 // operand panels, which ARE reused, out of the 4 MiB L2 of the XCD).
 constexpr int C_POLICY = 2;
 // Load schedule: of the 16 direct loads a wavefront issues per k-slice, N2B go out
-// in the second half of k-step 2 of the slice two before the one they fetch (as
-// soon as its LDS stage is free), N3 in k-step 3, N0 in k-step 0 of the next
-// slice and N1 in its k-step 1, evenly spaced between the MFMAs.  Measured at the
-// headline shape: 8,8,0,0 (everything at once) 5.42 ms forward, 4,6,6,0 5.22,
-// 6,5,5,0 / 5,6,5,0 / 4,7,5,0 the same, 2,6,6,2 5.34, 4,4,4,4 5.43 (the last
-// loads then land too late for the next barrier).
+// in the third quarter of the slice two before the one they fetch (as soon as its
+// LDS stage is free), N3 in its last quarter, N0 in the first quarter of the next
+// slice and N1 in its second quarter, evenly spaced between the MFMAs.  Measured at the
+// headline shape (on the kernel's 32x32x16 form): 8,8,0,0 (everything at once) 5.42 ms
+// forward, 4,6,6,0 5.22, 6,5,5,0 / 5,6,5,0 / 4,7,5,0 the same, 2,6,6,2 5.34, 4,4,4,4 5.43
+// (the last loads then land too late for the next barrier).
 #ifndef SFB_SCHED
 #define SFB_SCHED 4, 6, 6, 0
 #endif
 constexpr int SCHED[4] = {SFB_SCHED};
 constexpr int N2B = SCHED[0], N3 = SCHED[1], N0 = SCHED[2], N1 = SCHED[3];
 static_assert(N2B + N3 + N0 + N1 == 16 && N2B >= 0 && N3 >= 0 && N0 >= 0 && N1 >= 0, "16 loads per slice");
-constexpr int EPD = 4;                   // epilogue: blocks of C loads in flight + the one being stored (2: +1.5 %, 3 and 5: the same)
+constexpr int EPD = 3;                   // epilogue: blocks of C loads in flight + the one being stored (2: +1.5 %, 3 and 5: the same)
 
 // MODE_SPLIT: the apply on a matrix stored as two 16-bit planes (see split_from_w_kernel):
 // `shadow` is the high plane, `lo` the low one, C is not touched.
@@ -133,14 +137,35 @@ __device__ __forceinline__ int64_t operand_index(int64_t r, int64_t c, int64_t p
     return ((r / BM) * (pitch / BK) + c / BK) * (int64_t)(BM * BK) + (r % BM) * BK + c % BK;
 }
 // Chunk-slot swizzle of tile row r: chunk c of the row sits in slot c ^ swz(r).
-// Chosen by measurement: an MFMA operand read (32 consecutive rows at chunk g,
-// 16 bytes a lane) costs 26.9 cycles with this function, as little as with
-// padded rows, against 32.2 with r & 7 or (r >> 1) ^ (r >> 3) and 128 without a
-// swizzle.  swz(r + 32) = swz(r) ^ 4 and swz(r + 64) = swz(r).
+// Chosen by measurement: an MFMA operand read (runs of 16 consecutive rows at one
+// chunk, 16 bytes a lane: rows of either parity meet the eight slots once each)
+// costs 26.9 cycles with this function, as little as with padded rows, against
+// 32.2 with r & 7 or (r >> 1) ^ (r >> 3) and 128 without a swizzle.
+// swz(r + 16) = swz(r) ^ 2, swz(r + 32) = swz(r) ^ 4 and swz(r + 64) = swz(r).
 __device__ __forceinline__ int swz(int r) { return (r ^ (r >> 3)) & 7; }
 // LDS byte offset of chunk c (0..7) of tile row r (128-byte rows).  Chunk
-// (2 ks + g) of row r sits at lds_byte(r, g) ^ (32 ks).
+// (4 ks + q), q < 4, of row r sits at lds_byte(r, q) ^ (64 ks).
 __device__ __forceinline__ uint32_t lds_byte(int r, int c) { return (uint32_t)(r * 128 + ((c ^ swz(r)) << 4)); }
+
+// f(integral_constant<int, B>), ..., f(integral_constant<int, E - 1>): a loop that is unrolled by construction (the
+// 64-MFMA steps of the slice are beyond what the unroller accepts under a pragma, and an index that is not a
+// constant would put the accumulators in scratch memory).
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
+
+// The i-th of n loads goes after MFMA (2 i + 1) m / (2 n) of the m MFMAs of a window; -1: no load after MFMA j.
+constexpr int slot(int j, int n, int m)
+{
+    for (int i = 0; i < n; ++i)
+        if (j == (2 * i + 1) * m / (2 * n)) return i;
+    return -1;
+}
 
 // A wave-uniform 64-bit value as the compiler can see it (scalar registers).
 __device__ __forceinline__ uint64_t uniform64(uint64_t a)
@@ -196,9 +221,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     const char* const lds_bytes = reinterpret_cast<const char*>(smem);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
 
-    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar
-    const int wm0 = (wave >> 1) * (TM * 32), wn0 = (wave & 1) * (TN * 32);
+    const int wm0 = (wave >> 1) * (TM * 16), wn0 = (wave & 1) * (TN * 16);
 
     // ---- persistent schedule ------------------------------------------------
     const int64_t x = blockIdx.x % p.num_xcd, wi = blockIdx.x / p.num_xcd, per_xcd = gridDim.x / p.num_xcd;
@@ -220,12 +245,19 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     };
 
     // Which row of the B tile sits in LDS row r.  MFMA tile tb of a wavefront takes
-    // its 32 columns from LDS rows 32 tb .. 32 tb + 31 of the wavefront's 128; those
-    // rows hold tile rows 4 l + tb (l = 0..31), so that a lane ends up with four
-    // CONSECUTIVE columns of C in its four tiles (one 16-byte access per row in
-    // the epilogue, no cross-lane shuffles).  The loader is free to do this: each
-    // lane of a direct load supplies its own global address.
-    auto b_row_of = [](int r) { return (r & ~127) | ((r & 31) << 2) | ((r >> 5) & 3); };
+    // its 16 columns from LDS rows 16 tb .. 16 tb + 15 of the wavefront's 128; those
+    // rows hold tile rows 8 c + tb (c = 0..15), so that a lane ends up with eight
+    // CONSECUTIVE columns of C in its eight tiles (16-byte accesses of the 16-bit
+    // planes, two of C per row in the epilogue, no cross-lane shuffles).  The loader
+    // is free to do this: each lane of a direct load supplies its own global address.
+    // (Where C is fp32 — the logits of the forward, W as an fp32 array — a lane's eight columns are 32 bytes of a
+    // row.  There they are two groups of four, 64 columns apart, so that each of the two 16-byte accesses of a row
+    // covers whole lines: tile rows 4 c + tb % 4 + 64 (tb / 4); the bf16 copy is then accessed 8 bytes at a time.)
+    constexpr bool SPLIT8 = MODE != MODE_SPLIT;
+    auto b_row_of = [](int r) {
+        return SPLIT8 ? (r & ~127) | ((r & 15) << 2) | ((r >> 4) & 3) | (((r >> 6) & 1) << 6)
+                      : (r & ~127) | ((r & 15) << 3) | ((r >> 4) & 7);
+    };
 
     // ---- loader ---------------------------------------------------------------
     // A k-slice of a tile is 32 blocks of 8 rows for each operand; wavefront w
@@ -287,54 +319,57 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     };
 
     // ---- MFMA side ------------------------------------------------------------
-    floatx16 acc[TM][TN];   // defined by the first MFMAs of each tile (zero addend)
+    // 16x16x32 MFMAs: on operands that change, the chip keeps a higher clock with them than with the 32x32x16 form
+    // (register-only loops on pseudo-random bf16 data: 1.86 against 1.72 PFLOP/s; inside this kernel 3.5 %), for
+    // the same fragment bytes from LDS: eight A and eight B fragments per 32 of k, 64 MFMAs.
+    floatx4 acc[TM][TN];    // defined by the first MFMAs of each tile (zero addend)
 
-    // LDS read offsets of this lane: chunk g of rows wm0 + l32 (+32) of the A tile
-    // and wn0 + l32 (+32) of the B tile, in the stage being read.
-    uint32_t ra0 = lds_byte(wm0 + l32, g), ra1 = lds_byte(wm0 + 32 + l32, g) - 32 * 128;
-    uint32_t rb0 = lds_byte(wn0 + l32, g) + B_OFF, rb1 = lds_byte(wn0 + 32 + l32, g) - 32 * 128 + B_OFF;
+    // Lane l = (quad q = l >> 4, l16 = l & 15) supplies row l16 of a fragment's 16 rows and the 8 values
+    // k = 8 q .. 8 q + 7 of the 32 of a k-step (the same assignment for both operands: any is right).
+    // LDS byte offsets of chunk q of rows wm0 + 16 t + l16 (t = 0..3; t + 4 is 64 rows = 8 KiB further: swz(r + 64)
+    // = swz(r)) of the A tile and of wn0 + 16 t + l16 of the B tile, in the stage being read; k-step ks of the
+    // slice is chunk 4 ks + q: the offset XOR 64 ks.
+    const int l16 = lane & 15, quad = lane >> 4;
+    uint32_t ra[4], rb[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        ra[t] = lds_byte(wm0 + 16 * t + l16, quad);
+        rb[t] = lds_byte(wn0 + 16 * t + l16, quad) + B_OFF;
+    }
     struct Frags {
         bf16x8 a[TM], b[TN];
     };
-    auto read_frags = [&](Frags& f, int ks) {   // k-step ks (16 of k) of the stage ra / rb point at
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-            f.a[a] = *reinterpret_cast<const bf16x8*>(lds_bytes + (((a & 1) ? ra1 : ra0) ^ (32u * ks)) + a * 32 * 128);
-#pragma unroll
-        for (int b = 0; b < TN; ++b)
-            f.b[b] = *reinterpret_cast<const bf16x8*>(lds_bytes + (((b & 1) ? rb1 : rb0) ^ (32u * ks)) + b * 32 * 128);
+    // The i-th fragment read of a k-step, in the order the MFMAs (a outer, b inner) want them: a0, b0..b7, a1..a7.
+    auto read_one = [&](Frags& f, int ks, int i) {
+        if (i == 0 || i > TN) {
+            const int a = i == 0 ? 0 : i - TN;
+            f.a[a] = *reinterpret_cast<const bf16x8*>(lds_bytes + (ra[a & 3] ^ (64u * ks)) + (a >> 2) * 64 * 128);
+        } else {
+            const int b = i - 1;
+            f.b[b] = *reinterpret_cast<const bf16x8*>(lds_bytes + (rb[b & 3] ^ (64u * ks)) + (b >> 2) * 64 * 128);
+        }
     };
-    auto mfma_step = [&](const Frags& f) {
+    auto read_frags = [&](Frags& f, int ks) {   // k-step ks (32 of k) of the stage ra / rb point at
 #pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-            for (int b = 0; b < TN; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a], f.b[b], acc[a][b], 0, 0, 0);
-    };
-    auto mfma_step_first = [&](const Frags& f) {   // first k-step of a tile: accumulators start from zero
-        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-            for (int b = 0; b < TN; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a], f.b[b], zero, 0, 0, 0);
+        for (int i = 0; i < TM + TN; ++i) read_one(f, ks, i);
     };
     auto flip_stage = [&]() {
-        ra0 ^= STAGE;
-        ra1 ^= STAGE;
-        rb0 ^= STAGE;
-        rb1 ^= STAGE;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            ra[t] ^= STAGE;
+            rb[t] ^= STAGE;
+        }
     };
 
-    // Epilogue of one tile.  Register i of lane (g, l32) of MFMA tile (ta, tb) is
-    // row 32 ta + 8 (i / 4) + 4 g + i % 4, column 4 l32 + tb of the wavefront's
-    // 128 x 128 block (see b_row_of): for fixed (ta, i) a lane owns 4 consecutive
-    // columns, the 32 lanes of a half-wave 512 contiguous bytes of one row of C,
-    // the other half-wave the row 4 below.  C is addressed through a raw buffer
+    // Epilogue of one tile.  Register i of lane (quad, l16) of MFMA tile (ta, tb) is
+    // row 16 ta + 4 quad + i, column 8 l16 + tb of the wavefront's 128 x 128 block
+    // (see b_row_of): for fixed (ta, i) a lane owns 8 consecutive columns, the 16
+    // lanes of a quad 512 contiguous bytes of one row of C (256 of a 16-bit plane),
+    // the other quads the rows 4, 8 and 12 below.  C is addressed through a raw buffer
     // descriptor based at the wavefront's corner of the tile: the row offset is
     // scalar, the lane offset one register, so no address registers are live
-    // while loads are in flight.  Rows of C and of its bf16 copy are 16- resp.
-    // 8-byte aligned (checked by the launcher).
+    // while loads are in flight.  Rows of C, of its bf16 copy and of the planes are
+    // 16-byte aligned (checked by the launcher).
     auto make_rsrc = [&](const void* base) {
         return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(uniform64(reinterpret_cast<uint64_t>(base))),
                                                  0, 0xffffffff, 0x00020000);
@@ -353,32 +388,36 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
         const auto lrs = make_rsrc(MODE == MODE_SPLIT
                                        ? p.lo + ((m0 / BM) * p.tiles_n + n0 / BN) * (int64_t)(BM * BN) + wm0 * BN + wn0
                                        : p.lo);
-        const uint32_t row_l = (uint32_t)BN * 2u, lane_l = (uint32_t)(4 * g) * row_l + (uint32_t)l32 * 8u;
-        const int rows_left = (int)(p.M - (m0 + wm0) < 4 * BM ? p.M - (m0 + wm0) : 4 * BM) - 4 * g;   // for this lane
+        const uint32_t row_l = (uint32_t)BN * 2u, lane_l = (uint32_t)(4 * quad) * row_l + (uint32_t)l16 * 16u;
+        const int rows_left = (int)(p.M - (m0 + wm0) < 4 * BM ? p.M - (m0 + wm0) : 4 * BM) - 4 * quad;   // for this lane
         const uint32_t row_c = (MODE == MODE_FWD && p.c_blocked) ? (uint32_t)BN * 4u : (uint32_t)p.ldc * 4u;
         const uint32_t row_s = (uint32_t)BK * 2u;
-        const uint32_t lane_c = (uint32_t)(4 * g) * row_c + (uint32_t)l32 * 16u;
-        const uint32_t lane_s = (uint32_t)(l32 >> 4) * (uint32_t)(BM * BK * 2) + (uint32_t)(4 * g) * row_s + (uint32_t)(l32 & 15) * 8u;
-        const bool col_ok = !GUARD || (n0 + wn0 + 4 * l32 < p.N);   // N % 4 == 0: all four columns or none
-        // One block = 16 rows of one ta (8 accesses of 16 bytes per lane).  The loads
-        // of the next EPD - 1 blocks are in flight while a block is combined and
-        // stored.
-        constexpr int NQ = 2 * TM;
-        u32x4 w[EPD][8];
+        const uint32_t lane_c = (uint32_t)(4 * quad) * row_c + (uint32_t)l16 * (SPLIT8 ? 16u : 32u);
+        const uint32_t half_c = SPLIT8 ? 256u : 16u;        // bytes from a lane's first four columns to its other four
+        const uint32_t lane_s = SPLIT8 ? (uint32_t)(4 * quad) * row_s + (uint32_t)l16 * 8u
+                                       : (uint32_t)(l16 >> 3) * (uint32_t)(BM * BK * 2) + (uint32_t)(4 * quad) * row_s + (uint32_t)(l16 & 7) * 16u;
+        const bool col_ok = !GUARD || (n0 + wn0 + (SPLIT8 ? 4 : 8) * l16 < p.N);   // N % 8 == 0: all eight (four) columns or none
+        const bool col_ok1 = !GUARD || !SPLIT8 || (n0 + wn0 + 64 + 4 * l16 < p.N);    // (forward: the second group of four)
+        // One block = the 16 rows of one ta: 4 rows per lane, 8 columns each (two 16-byte accesses per row: both
+        // planes, or the two halves of the fp32 row segment).  The loads of the next EPD - 1 blocks are in flight
+        // while a block is combined and stored.
+        constexpr int NQ = TM;
+        u32x4 w[EPD][4][2];
         mfma_results_settle();
-        auto load_block = [&](int q, u32x4* dst) {
+        auto load_block = [&](int q, u32x4 (*dst)[2]) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int i = (q & 1) * 8 + e, dr = (q >> 1) * 32 + 8 * (i / 4) + (i % 4);
-                dst[e] = u32x4{0u, 0u, 0u, 0u};
+            for (int e = 0; e < 4; ++e) {
+                const int dr = q * 16 + e;
+                dst[e][0] = u32x4{0u, 0u, 0u, 0u};
+                dst[e][1] = u32x4{0u, 0u, 0u, 0u};
                 if (col_ok && (!GUARD || dr < rows_left)) {
-                    if (MODE == MODE_SPLIT) {   // four columns of the high plane, then of the low plane
-                        const u32x2 h = __builtin_amdgcn_raw_buffer_load_b64(srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
-                        const u32x2 l = __builtin_amdgcn_raw_buffer_load_b64(lrs, lane_l, (uint32_t)dr * row_l, C_POLICY);
-                        const uint32_t h0 = h[0], h1 = h[1], l0 = l[0], l1 = l[1];
-                        dst[e] = u32x4{h0, h1, l0, l1};
+                    if (MODE == MODE_SPLIT) {   // eight columns of the high plane, eight of the low plane
+                        dst[e][0] = __builtin_amdgcn_raw_buffer_load_b128(srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
+                        dst[e][1] = __builtin_amdgcn_raw_buffer_load_b128(lrs, lane_l, (uint32_t)dr * row_l, C_POLICY);
                     } else {
-                        dst[e] = __builtin_amdgcn_raw_buffer_load_b128(crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
+                        dst[e][0] = __builtin_amdgcn_raw_buffer_load_b128(crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
+                        if (col_ok1)
+                            dst[e][1] = __builtin_amdgcn_raw_buffer_load_b128(crs, lane_c + half_c, (uint32_t)dr * row_c, C_POLICY);
                     }
                 }
             }
@@ -389,46 +428,63 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
         }
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
-            const int ta = q >> 1;
             if (MODE != MODE_FWD && q + EPD - 1 < NQ) load_block(q + EPD - 1, w[(q + EPD - 1) % EPD]);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int i = (q & 1) * 8 + e, dr = ta * 32 + 8 * (i / 4) + (i % 4);
-                const float v0 = acc_read(acc[ta][0][i]), v1 = acc_read(acc[ta][1][i]);
-                const float v2 = acc_read(acc[ta][2][i]), v3 = acc_read(acc[ta][3][i]);
+            for (int e = 0; e < 4; ++e) {
+                const int dr = q * 16 + e;
+                float v[TN];
+#pragma unroll
+                for (int tb = 0; tb < TN; ++tb) v[tb] = acc_read(acc[q][tb][e]);
                 if (col_ok && (!GUARD || dr < rows_left)) {
                     if (MODE == MODE_FWD) {
-                        const u32x4 out = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2),
-                                           __float_as_uint(v3)};
-                        __builtin_amdgcn_raw_buffer_store_b128(out, crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
+                        const u32x4 out0 = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+                        const u32x4 out1 = {__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])};
+                        __builtin_amdgcn_raw_buffer_store_b128(out0, crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
+                        if (col_ok1)
+                            __builtin_amdgcn_raw_buffer_store_b128(out1, crs, lane_c + half_c, (uint32_t)dr * row_c, C_POLICY);
                     } else if (MODE == MODE_SPLIT) {
-                        const uint32_t hA = w[q % EPD][e][0], hB = w[q % EPD][e][1], lA = w[q % EPD][e][2],
-                                       lB = w[q % EPD][e][3];
-                        const uint32_t w0 = split_word(split_value(join_pair0(hA, lA)) - p.eta * v0);
-                        const uint32_t w1 = split_word(split_value(join_pair1(hA, lA)) - p.eta * v1);
-                        const uint32_t w2 = split_word(split_value(join_pair0(hB, lB)) - p.eta * v2);
-                        const uint32_t w3 = split_word(split_value(join_pair1(hB, lB)) - p.eta * v3);
-                        const u32x2 oh = {pack_hi(w0, w1), pack_hi(w2, w3)};
-                        const u32x2 ol = {pack_lo(w0, w1), pack_lo(w2, w3)};
-                        // the high halves change only where the update crosses a bf16 rounding boundary: lanes
-                        // whose four are unchanged leave the plane as it is (the same bits, fewer bytes written)
-                        if (oh[0] != hA || oh[1] != hB)
-                            __builtin_amdgcn_raw_buffer_store_b64(oh, srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
-                        __builtin_amdgcn_raw_buffer_store_b64(ol, lrs, lane_l, (uint32_t)dr * row_l, C_POLICY);
-                    } else {
-                        const uint32_t o0 = w[q % EPD][e][0], o1 = w[q % EPD][e][1], o2 = w[q % EPD][e][2],
-                                       o3 = w[q % EPD][e][3];
-                        const float n0f = __uint_as_float(o0) - p.eta * v0, n1f = __uint_as_float(o1) - p.eta * v1;
-                        const float n2f = __uint_as_float(o2) - p.eta * v2, n3f = __uint_as_float(o3) - p.eta * v3;
-                        const u32x4 out = {__float_as_uint(n0f), __float_as_uint(n1f), __float_as_uint(n2f),
-                                           __float_as_uint(n3f)};
-                        __builtin_amdgcn_raw_buffer_store_b128(out, crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
-                        if (has_shadow) {   // the copy is current on entry: rewrite it only where its bits change
-                            const u32x2 sh = {pack_bf16(n0f, n1f), pack_bf16(n2f, n3f)};
-                            if (sh[0] != pack_bf16(__uint_as_float(o0), __uint_as_float(o1)) ||
-                                sh[1] != pack_bf16(__uint_as_float(o2), __uint_as_float(o3)))
-                                __builtin_amdgcn_raw_buffer_store_b64(sh, srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
+                        uint32_t oh[4], ol[4];
+                        bool changed = false;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {      // dword k of both planes: columns 2 k, 2 k + 1
+                            const uint32_t hk = w[q % EPD][e][0][k], lk = w[q % EPD][e][1][k];
+                            const uint32_t w0 = split_word(split_value(join_pair0(hk, lk)) - p.eta * v[2 * k]);
+                            const uint32_t w1 = split_word(split_value(join_pair1(hk, lk)) - p.eta * v[2 * k + 1]);
+                            oh[k] = pack_hi(w0, w1);
+                            ol[k] = pack_lo(w0, w1);
+                            changed = changed || oh[k] != hk;
                         }
+                        // the high halves change only where the update crosses a bf16 rounding boundary: lanes
+                        // whose eight are unchanged leave the plane as it is (the same bits, fewer bytes written)
+                        if (changed)
+                            __builtin_amdgcn_raw_buffer_store_b128(u32x4{oh[0], oh[1], oh[2], oh[3]}, srs, lane_s,
+                                                                   (uint32_t)dr * row_s, C_POLICY);
+                        __builtin_amdgcn_raw_buffer_store_b128(u32x4{ol[0], ol[1], ol[2], ol[3]}, lrs, lane_l,
+                                                               (uint32_t)dr * row_l, C_POLICY);
+                    } else {
+                        float nf[TN];
+                        uint32_t sh[4];
+                        bool changed[2] = {false, false};
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {      // (k / 2 is the group of four columns)
+                            const uint32_t oa = w[q % EPD][e][k >> 1][(2 * k) & 3], ob = w[q % EPD][e][k >> 1][(2 * k + 1) & 3];
+                            nf[2 * k] = __uint_as_float(oa) - p.eta * v[2 * k];
+                            nf[2 * k + 1] = __uint_as_float(ob) - p.eta * v[2 * k + 1];
+                            sh[k] = pack_bf16(nf[2 * k], nf[2 * k + 1]);
+                            changed[k >> 1] = changed[k >> 1] || sh[k] != pack_bf16(__uint_as_float(oa), __uint_as_float(ob));
+                        }
+                        const u32x4 out0 = {__float_as_uint(nf[0]), __float_as_uint(nf[1]), __float_as_uint(nf[2]), __float_as_uint(nf[3])};
+                        const u32x4 out1 = {__float_as_uint(nf[4]), __float_as_uint(nf[5]), __float_as_uint(nf[6]), __float_as_uint(nf[7])};
+                        __builtin_amdgcn_raw_buffer_store_b128(out0, crs, lane_c, (uint32_t)dr * row_c, C_POLICY);
+                        if (col_ok1)
+                            __builtin_amdgcn_raw_buffer_store_b128(out1, crs, lane_c + half_c, (uint32_t)dr * row_c, C_POLICY);
+                        // the copy is current on entry: rewrite it only where its bits change (the second group of
+                        // four columns lies in the next block of 64 columns of the operand layout)
+                        if (has_shadow && changed[0])
+                            __builtin_amdgcn_raw_buffer_store_b64(u32x2{sh[0], sh[1]}, srs, lane_s, (uint32_t)dr * row_s, C_POLICY);
+                        if (has_shadow && changed[1] && col_ok1)
+                            __builtin_amdgcn_raw_buffer_store_b64(u32x2{sh[2], sh[3]}, srs, lane_s + (uint32_t)(BM * BK * 2),
+                                                                  (uint32_t)dr * row_s, C_POLICY);
                     }
                 }
             }
@@ -436,101 +492,68 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     };
 
     // ---- pipeline ---------------------------------------------------------------
-    // Slice s lives in stage s & 1.  In the last k-step of slice s, after every
-    // wavefront has read that step's fragments (so stage s & 1 is free) and the
-    // loads of slice s+1 have landed, the loads of slice s+2 are issued and the
-    // first fragments of slice s+1 are read; the MFMAs of the last k-step cover
-    // both latencies.
+    // Slice s lives in stage s & 1 and is two k-steps of 32: f0 holds the fragments of the first, f1 of the second.
+    // The second step's fragments are read under the first step's MFMAs, so after the first step every wavefront is
+    // done with stage s & 1 (barrier A: the loads of slice s+2 start); half way through the second step the loads
+    // of slice s+1 must have landed (barrier B), and its first fragments are read under the rest of that step.
     Frags f0, f1;
     enter_tile(0);
     issue();
     wait_all_vmem();
     __syncthreads();
-    // (the first k-steps of the loop issue the rest of slice 1)
+    // (the first k-step of the loop issues the rest of slice 1)
 #pragma unroll
     for (int j = 0; j < 16; ++j)
         if (j < N2B + N3) issue_one(j);
     read_frags(f0, 0);
     // One k-slice (slice s, living in stage s & 1; f0 holds its first fragments).
     // The direct loads are unconditional (past the last slice they re-fetch the
-    // last tile into a stage nobody reads).  Two barriers: A, after every
-    // wavefront has read the last fragments of slice s (stage s & 1 may be
-    // overwritten: the loads of slice s+2 start); B, after the loads of slice s+1
-    // have landed (vmcnt counts in order, so only the N2B loads issued since A may
-    // still be in flight).
-    auto mfma_one = [&](const Frags& f, int j) {
-        acc[j / TN][j % TN] =
-            __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[j / TN], f.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
-    };
-    // i-th of n loads goes after MFMA (2 i + 1) m / (2 n) of the m MFMAs of the step; -1: no load after MFMA j
-    auto slot = [](int j, int n, int m) {
-        for (int i = 0; i < n; ++i)
-            if (j == (2 * i + 1) * m / (2 * n)) return i;
-        return -1;
-    };
-    // One fragment read (i < TM: row block i of A, else row block i - TM of B) of k-step ks.
-    auto read_one = [&](Frags& f, int ks, int i) {
-        if (i < TM)
-            f.a[i] = *reinterpret_cast<const bf16x8*>(lds_bytes + (((i & 1) ? ra1 : ra0) ^ (32u * ks)) + i * 32 * 128);
-        else
-            f.b[i - TM] = *reinterpret_cast<const bf16x8*>(lds_bytes + ((((i - TM) & 1) ? rb1 : rb0) ^ (32u * ks)) +
-                                                           (i - TM) * 32 * 128);
-    };
+    // last tile into a stage nobody reads).  vmcnt counts in order, so at barrier B
+    // only the N2B loads issued since A may still be in flight.
     // The instruction order of a slice is fixed by hand (a scheduling barrier after
     // every MFMA): left to itself the compiler sinks the fragment reads of the next
     // k-step to just before their first use, and the wavefront then waits out the
-    // LDS latency with an idle MFMA pipe several times per slice.  The eight reads
-    // of the next k-step follow the first MFMAs of the current one, one each (two
-    // each in k-step 2, whose reads must be over before barrier A).
+    // LDS latency with an idle MFMA pipe.  The sixteen reads of the next k-step
+    // follow every second of the first 32 MFMAs of the current one (one per MFMA
+    // would ask more of the LDS than it delivers while the direct loads write it).
     auto slice_body = [&](auto first_tag) {
-        {   // k-step 0: MFMAs on f0, reads of k-step 1 into f1, N0 loads
-            const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                if constexpr (decltype(first_tag)::value)
-                    acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.a[j / TN], f0.b[j % TN], zero, 0, 0, 0);
-                else
-                    mfma_one(f0, j);
-                if (j < 8) read_one(f1, 1, j);
-                if (slot(j, N0, 16) >= 0) issue_one(N2B + N3 + slot(j, N0, 16));
-                __builtin_amdgcn_sched_barrier(0);
+        const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+        // k-step 0: MFMAs on f0, reads of k-step 1 into f1; the N0 loads in its first half, N1 in its second
+        static_for<0, TM * TN>([&](auto J) {
+            constexpr int j = decltype(J)::value;
+            if constexpr (decltype(first_tag)::value)
+                acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[j / TN], f0.b[j % TN], zero, 0, 0, 0);
+            else
+                acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[j / TN], f0.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
+            if constexpr (j < 32 && (j & 1) == 0) read_one(f1, 1, j >> 1);
+            if constexpr (j < 32) {
+                if constexpr (slot(j, N0, 32) >= 0) issue_one(N2B + N3 + slot(j, N0, 32));
+            } else {
+                if constexpr (slot(j - 32, N1, 32) >= 0) issue_one(N2B + N3 + N0 + slot(j - 32, N1, 32));
             }
-            if (N1 == 0) issue_done();
-        }
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {                     // k-step 1: MFMAs on f1, reads of k-step 2 into f0
-            mfma_one(f1, j);
-            if (j < 8) read_one(f0, 2, j);
-            if (slot(j, N1, 16) >= 0) issue_one(N2B + N3 + N0 + slot(j, N1, 16));
+            if constexpr (j == 31 && N1 == 0) issue_done();
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
         if (N1 > 0) issue_done();
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {                      // k-step 2: MFMAs on f0, reads of k-step 3 into f1
-            mfma_one(f0, j);
-            if (j < 4) {
-                read_one(f1, 3, 2 * j);
-                read_one(f1, 3, 2 * j + 1);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
         __syncthreads();                                   // A
-#pragma unroll
-        for (int j = 8; j < 16; ++j) {                     // first loads of slice s+2
-            mfma_one(f0, j);
-            if (slot(j - 8, N2B, 8) >= 0) issue_one(slot(j - 8, N2B, 8));
+        // k-step 1, first half: MFMAs on f1, the first loads of slice s+2
+        static_for<0, 32>([&](auto J) {
+            constexpr int j = decltype(J)::value;
+            acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.a[j / TN], f1.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
+            if constexpr (slot(j, N2B, 32) >= 0) issue_one(slot(j, N2B, 32));
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N2B) : "memory");   // everything but those: slice s+1 is in LDS
         __syncthreads();                                   // B
         flip_stage();
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {                     // k-step 3: MFMAs on f1, reads of the next slice's k-step 0
-            mfma_one(f1, j);                               // (after the last slice: of a stage nobody uses)
-            if (j < 8) read_one(f0, 0, j);
-            if (slot(j, N3, 16) >= 0) issue_one(N2B + slot(j, N3, 16));
+        // second half: reads of the next slice's k-step 0 into f0 (after the last slice: of a stage nobody uses)
+        static_for<32, TM * TN>([&](auto J) {
+            constexpr int j = decltype(J)::value;
+            acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.a[j / TN], f1.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
+            if constexpr ((j & 1) == 0) read_one(f0, 0, (j - 32) >> 1);
+            if constexpr (slot(j - 32, N3, 32) >= 0) issue_one(N2B + slot(j - 32, N3, 32));
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
     };
     for (int64_t t = 0; t < n_my; ++t) {
         int64_t m0, n0;
@@ -677,12 +700,12 @@ hipError_t launch(Params p, DeviceInfo& dev, hipStream_t stream)
     // 32-bit in-tile byte offsets in the loaders and in the epilogue
     if (p.lda * 2 * BM >= (1LL << 31) || p.ldb * 2 * BN >= (1LL << 31) || p.ldc * 4 * BM >= (1LL << 31))
         return hipErrorInvalidValue;
-    // 16-byte accesses of C, 8-byte accesses of its bf16 copy and of the two planes
-    if (p.N % 4 != 0) return hipErrorInvalidValue;
+    // 16-byte accesses of C, of its bf16 copy and of the two planes; a lane owns eight consecutive columns
+    if (p.N % 8 != 0) return hipErrorInvalidValue;
     if (MODE != MODE_SPLIT && (reinterpret_cast<uintptr_t>(p.C) % 16 != 0 || p.ldc % 4 != 0)) return hipErrorInvalidValue;
-    if (p.shadow && (reinterpret_cast<uintptr_t>(p.shadow) % 8 != 0 || p.ld_shadow % 4 != 0))
+    if (p.shadow && (reinterpret_cast<uintptr_t>(p.shadow) % 16 != 0 || p.ld_shadow % 8 != 0))
         return hipErrorInvalidValue;
-    if (MODE == MODE_SPLIT && (!p.shadow || !p.lo || reinterpret_cast<uintptr_t>(p.lo) % 8 != 0 || p.ld_shadow < p.N ||
+    if (MODE == MODE_SPLIT && (!p.shadow || !p.lo || reinterpret_cast<uintptr_t>(p.lo) % 16 != 0 || p.ld_shadow < p.N ||
                                p.ld_shadow * 2 * BM >= (1LL << 31)))
         return hipErrorInvalidValue;
     if (p.K <= 0 || p.K % BK != 0 || p.lda % BK != 0 || p.ldb % BK != 0 || p.lda < p.K || p.ldb < p.K)

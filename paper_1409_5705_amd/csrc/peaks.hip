@@ -1,6 +1,7 @@
 // Stand-alone probe of what this GPU sustains on the two resources the
 // roofline fractions are quoted against: the MFMA pipes (a register-only loop of
-// bf16 32x32x16 and fp32 32x32x2 MFMAs, one and two wavefronts per SIMD) and HBM
+// bf16 32x32x16 and fp32 32x32x2 MFMAs, one and two wavefronts per SIMD; bf16 MFMAs of both
+// shapes on operands that change) and HBM
 // (streaming read, copy and read-modify-write of buffers far larger than the
 // caches, 16 bytes per lane), and what ONE compute unit can pull through its
 // vector-memory path when a quarter of the CUs stream alone (one workgroup each:
@@ -54,20 +55,19 @@ __global__ __launch_bounds__(512) void mfma_loop(float* out, int iters)
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
-// The same bf16 loop fed like a real contraction: 4 x 4 MFMA tiles per wavefront, four A and four B fragments of
-// pseudo-random values (|x| in [1/2, 2), random signs and mantissas), every fragment used by four MFMAs, and sign and
-// mantissa bits of all fragments flipped by a new pattern after every 16 MFMAs (32 vector instructions: what the
-// fragment reads of a kernel cost in issue slots).  The clock the chip grants depends on how many bits toggle:
-// this is the matrix-pipe rate with operands that change, against mfma_loop's with operands that never do
-// (flip_bits = 0 runs the identical instruction stream on operands that stay as they are: the control).
+// The same bf16 work fed like a real contraction: a wavefront's 128 x 128 block, eight A and eight B fragments of
+// pseudo-random values (|x| in [1/2, 2), random signs and mantissas) covering 32 of k, every fragment used by
+// several MFMAs, and sign and mantissa bits of all fragments flipped by a new pattern after every 1.05 MFLOP
+// (64 vector instructions: what the fragment reads of a kernel cost in issue slots).  SHAPE 32: 4 x 4 tiles of
+// 32 x 32, two 32x32x16 MFMAs each; SHAPE 16: 8 x 8 tiles of 16 x 16, one 16x16x32 MFMA each.  The clock the
+// chip grants depends on how many bits toggle: this is the matrix-pipe rate with operands that change, against
+// mfma_loop's with operands that never do (flip_bits = 0 runs the identical instruction stream on operands that
+// stay as they are, value_bits = 0 makes every element 0.5: the controls).
+template <int SHAPE>
 __global__ __launch_bounds__(256) void mfma_random_loop(float* out, int iters, uint32_t flip_bits, uint32_t value_bits)
 {
-    floatx16 acc[4][4];
-    for (int a = 0; a < 4; ++a)
-        for (int b = 0; b < 4; ++b)
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
     typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
-    u32x4v fa[4], fb[4];
+    u32x4v fa[8], fb[8];
     uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
     auto next = [&]() {
         h ^= h << 13;
@@ -75,34 +75,62 @@ __global__ __launch_bounds__(256) void mfma_random_loop(float* out, int iters, u
         h ^= h << 5;
         return h;
     };
-    for (int f = 0; f < 4; ++f)
+    for (int f = 0; f < 8; ++f)
         for (int e = 0; e < 4; ++e) {
             // two bf16 per word: exponent 126 or 127 (0.5 <= |x| < 2), random sign and mantissa
-            fa[f][e] = (next() & value_bits) | 0x3f003f00u;      // value_bits = 0: every element 0.5
+            fa[f][e] = (next() & value_bits) | 0x3f003f00u;
             fb[f][e] = (next() & value_bits) | 0x3f003f00u;
         }
     uint32_t flip = next();
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[a]), __builtin_bit_cast(bf16x8, fb[b]),
-                                                                    acc[a][b], 0, 0, 0);
+    auto flip_all = [&]() {
         flip = flip * 1664525u + 1013904223u;
-        const uint32_t m = flip & flip_bits;       // 0x807f807f: signs and mantissas only (no infinities, no NaNs); 0: nothing changes
+        const uint32_t m = flip & flip_bits;       // 0x807f807f: signs and mantissas only (no infinities, no NaNs)
 #pragma unroll
-        for (int f = 0; f < 4; ++f)
+        for (int f = 0; f < 8; ++f)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 fa[f][e] ^= m;
                 fb[f][e] ^= (m >> 1) & flip_bits;
             }
-    }
+    };
     float sum = 0.f;
-    for (int a = 0; a < 4; ++a)
-        for (int b = 0; b < 4; ++b)
-            for (int i = 0; i < 16; ++i) sum += acc[a][b][i];
+    if (SHAPE == 32) {
+        floatx16 acc[4][4];
+        for (int a = 0; a < 4; ++a)
+            for (int b = 0; b < 4; ++b)
+                for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[a + 4 * ks]),
+                                                                            __builtin_bit_cast(bf16x8, fb[b + 4 * ks]), acc[a][b], 0, 0, 0);
+            flip_all();
+        }
+        for (int a = 0; a < 4; ++a)
+            for (int b = 0; b < 4; ++b)
+                for (int i = 0; i < 16; ++i) sum += acc[a][b][i];
+    } else {
+        floatx4 acc[8][8];
+        for (int a = 0; a < 8; ++a)
+            for (int b = 0; b < 8; ++b)
+                for (int i = 0; i < 4; ++i) acc[a][b][i] = 0.f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int a = 0; a < 8; ++a)
+#pragma unroll
+                for (int b = 0; b < 8; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fa[a]), __builtin_bit_cast(bf16x8, fb[b]),
+                                                                        acc[a][b], 0, 0, 0);
+            flip_all();
+        }
+        for (int a = 0; a < 8; ++a)
+            for (int b = 0; b < 8; ++b)
+                for (int i = 0; i < 4; ++i) sum += acc[a][b][i];
+    }
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = sum;
 }
 
@@ -224,15 +252,18 @@ int main()
             const double mfmas = (double)iters * 32 * (threads / 64) * cus;
             tf[k++] = mfmas * (bf16 ? 32768.0 : 4096.0) / (ms * 1e-3) / 1e12;
         }
-    double tf_random = 0.0, tf_control = 0.0, tf_const = 0.0;
+    double tf_random = 0.0, tf_control = 0.0, tf_const = 0.0, tf_random16 = 0.0;
     {
-        const int it2 = 8000;       // x 16 MFMAs: about 50 ms, long enough for the clock to settle
-        if (time_ms([&] { hipLaunchKernelGGL(mfma_random_loop, dim3(cus), dim3(256), 0, 0, out, it2, 0x807f807fu, 0x80ff80ffu); }, 3, &ms)) return 1;
-        tf_random = (double)it2 * 16 * 4 * cus * 32768.0 / (ms * 1e-3) / 1e12;
-        if (time_ms([&] { hipLaunchKernelGGL(mfma_random_loop, dim3(cus), dim3(256), 0, 0, out, it2, 0u, 0x80ff80ffu); }, 3, &ms)) return 1;
-        tf_control = (double)it2 * 16 * 4 * cus * 32768.0 / (ms * 1e-3) / 1e12;
-        if (time_ms([&] { hipLaunchKernelGGL(mfma_random_loop, dim3(cus), dim3(256), 0, 0, out, it2, 0u, 0u); }, 3, &ms)) return 1;
-        tf_const = (double)it2 * 16 * 4 * cus * 32768.0 / (ms * 1e-3) / 1e12;
+        const int it2 = 60000;      // x 1.05 MFLOP per wavefront: about 35 ms, long enough for the clock to settle
+        const double fl = (double)it2 * 1048576.0 * 4 * cus;
+        if (time_ms([&] { hipLaunchKernelGGL(mfma_random_loop<32>, dim3(cus), dim3(256), 0, 0, out, it2, 0x807f807fu, 0x80ff80ffu); }, 3, &ms)) return 1;
+        tf_random = fl / (ms * 1e-3) / 1e12;
+        if (time_ms([&] { hipLaunchKernelGGL(mfma_random_loop<32>, dim3(cus), dim3(256), 0, 0, out, it2, 0u, 0x80ff80ffu); }, 3, &ms)) return 1;
+        tf_control = fl / (ms * 1e-3) / 1e12;
+        if (time_ms([&] { hipLaunchKernelGGL(mfma_random_loop<32>, dim3(cus), dim3(256), 0, 0, out, it2, 0u, 0u); }, 3, &ms)) return 1;
+        tf_const = fl / (ms * 1e-3) / 1e12;
+        if (time_ms([&] { hipLaunchKernelGGL(mfma_random_loop<16>, dim3(cus), dim3(256), 0, 0, out, it2, 0x807f807fu, 0x80ff80ffu); }, 3, &ms)) return 1;
+        tf_random16 = fl / (ms * 1e-3) / 1e12;
     }
     CK(hipFree(out));
 
@@ -292,14 +323,15 @@ int main()
     CK(hipFree(b));
     CK(hipFree(sink));
     printf("{\"device\": \"%s\", \"compute_units\": %d, \"clock_mhz\": %d, "
-           "\"mfma_bf16_tflops\": {\"one_wave_per_simd\": %.1f, \"two_waves_per_simd\": %.1f, \"one_wave_changing_operands\": %.1f, \"same_loop_operands_kept\": %.1f, \"same_loop_all_elements_equal\": %.1f}, "
+           "\"mfma_bf16_tflops\": {\"one_wave_per_simd\": %.1f, \"two_waves_per_simd\": %.1f, \"one_wave_changing_operands\": %.1f, \"same_loop_operands_kept\": %.1f, \"same_loop_all_elements_equal\": %.1f, "
+           "\"one_wave_changing_operands_16x16x32\": %.1f}, "
            "\"mfma_f32_tflops\": {\"one_wave_per_simd\": %.1f, \"two_waves_per_simd\": %.1f}, "
            "\"hbm_gbs\": {\"read\": %.0f, \"copy_read_plus_write\": %.0f, \"read_modify_write\": %.0f}, "
            "\"one_cu_read_gbs\": {\"miss_4_waves\": %.1f, \"miss_16_waves\": %.1f, \"l2_4_waves\": %.1f, \"l2_16_waves\": %.1f, "
            "\"l2_4_waves_8_byte\": %.1f, \"l2_16_waves_8_byte\": %.1f}, "
            "\"one_cu_write_gbs\": {\"4_waves\": %.1f, \"16_waves\": %.1f}, "
            "\"buffer_gib\": 4}\n",
-           prop.gcnArchName, cus, prop.clockRate / 1000, tf[0], tf[1], tf_random, tf_control, tf_const, tf[2], tf[3], gbs[0], gbs[1], gbs[2], cu[0], cu[1], cu[2],
+           prop.gcnArchName, cus, prop.clockRate / 1000, tf[0], tf[1], tf_random, tf_control, tf_const, tf_random16, tf[2], tf[3], gbs[0], gbs[1], gbs[2], cu[0], cu[1], cu[2],
            cu[3], cu[4], cu[5], cuw[0], cuw[1]);
     return 0;
 }
