@@ -79,15 +79,26 @@ constexpr int C_POLICY = 2;
 // in the third quarter of the slice two before the one they fetch (as soon as its
 // LDS stage is free), N3 in its last quarter, N0 in the first quarter of the next
 // slice and N1 in its second quarter, evenly spaced between the MFMAs.  Measured at the
-// headline shape (on the kernel's 32x32x16 form): 8,8,0,0 (everything at once) 5.42 ms
-// forward, 4,6,6,0 5.22, 6,5,5,0 / 5,6,5,0 / 4,7,5,0 the same, 2,6,6,2 5.34, 4,4,4,4 5.43
-// (the last loads then land too late for the next barrier).
+// headline shape, forward / apply in ms, interleaved on one box: 8,8,0,0 4.32 / 6.24,
+// 7,7,2,0 and 10,6,0,0 4.30 / 6.24, 6,10,0,0 4.32 / 6.25, 8,6,2,0 and 6,8,2,0 4.31 / 6.27,
+// 5,8,3,0 4.37 / 6.28, 6,5,5,0 4.43 / 6.29, 4,6,6,0 4.53 / 6.35, 3,6,7,0 4.62 / 6.37, 2,6,6,2
+// 4.89 / 6.38, 4,4,4,4 4.97 / 6.54: what is issued in the first half of the next slice has
+// too little time left before that slice's barrier B.
 #ifndef SFB_SCHED
-#define SFB_SCHED 4, 6, 6, 0
+#define SFB_SCHED 8, 8, 0, 0
 #endif
+#ifndef SFB_APOS
+#define SFB_APOS 64
+#endif
+#ifndef SFB_BPOS
+#define SFB_BPOS 32
+#endif
+// Barrier A after APOS of the 64 MFMAs of a slice's first k-step, barrier B after BPOS of those of the second.
+constexpr int APOS = SFB_APOS, BPOS = SFB_BPOS;
 constexpr int SCHED[4] = {SFB_SCHED};
 constexpr int N2B = SCHED[0], N3 = SCHED[1], N0 = SCHED[2], N1 = SCHED[3];
 static_assert(N2B + N3 + N0 + N1 == 16 && N2B >= 0 && N3 >= 0 && N0 >= 0 && N1 >= 0, "16 loads per slice");
+static_assert(APOS >= 40 && APOS <= 64 && (APOS == 64 || N1 == 0) && BPOS >= 0 && BPOS <= 48 && (64 - BPOS) % 16 == 0, "barrier positions");
 constexpr int EPD = 3;                   // epilogue: blocks of C loads in flight + the one being stored (2: +1.5 %, 3 and 5: the same)
 
 // MODE_SPLIT: the apply on a matrix stored as two 16-bit planes (see split_from_w_kernel):
@@ -518,8 +529,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     // would ask more of the LDS than it delivers while the direct loads write it).
     auto slice_body = [&](auto first_tag) {
         const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
-        // k-step 0: MFMAs on f0, reads of k-step 1 into f1; the N0 loads in its first half, N1 in its second
-        static_for<0, TM * TN>([&](auto J) {
+        constexpr int STEP = TM * TN;          // MFMAs of a k-step
+        // MFMAs 0 .. APOS-1: k-step 0 on f0 (the reads of k-step 1 into f1 behind every second of the first 32)
+        static_for<0, APOS>([&](auto J) {
             constexpr int j = decltype(J)::value;
             if constexpr (decltype(first_tag)::value)
                 acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[j / TN], f0.b[j % TN], zero, 0, 0, 0);
@@ -531,27 +543,34 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             } else {
                 if constexpr (slot(j - 32, N1, 32) >= 0) issue_one(N2B + N3 + N0 + slot(j - 32, N1, 32));
             }
-            if constexpr (j == 31 && N1 == 0) issue_done();
             __builtin_amdgcn_sched_barrier(0);
         });
-        if (N1 > 0) issue_done();
+        issue_done();
         __syncthreads();                                   // A
-        // k-step 1, first half: MFMAs on f1, the first loads of slice s+2
-        static_for<0, 32>([&](auto J) {
-            constexpr int j = decltype(J)::value;
-            acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.a[j / TN], f1.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
-            if constexpr (slot(j, N2B, 32) >= 0) issue_one(slot(j, N2B, 32));
+        // MFMAs APOS .. STEP+BPOS-1: the rest of k-step 0, the first BPOS of k-step 1 on f1; the first loads of slice s+2
+        static_for<APOS, STEP + BPOS>([&](auto J) {
+            constexpr int m = decltype(J)::value, j = m % STEP;
+            if constexpr (m < STEP) {
+                if constexpr (decltype(first_tag)::value)
+                    acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[j / TN], f0.b[j % TN], zero, 0, 0, 0);
+                else
+                    acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[j / TN], f0.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
+            } else {
+                acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.a[j / TN], f1.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
+            }
+            if constexpr (slot(m - APOS, N2B, STEP + BPOS - APOS) >= 0) issue_one(slot(m - APOS, N2B, STEP + BPOS - APOS));
             __builtin_amdgcn_sched_barrier(0);
         });
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N2B) : "memory");   // everything but those: slice s+1 is in LDS
         __syncthreads();                                   // B
         flip_stage();
-        // second half: reads of the next slice's k-step 0 into f0 (after the last slice: of a stage nobody uses)
-        static_for<32, TM * TN>([&](auto J) {
+        // the rest of k-step 1: reads of the next slice's k-step 0 into f0 (after the last slice: of a stage nobody uses)
+        static_for<BPOS, STEP>([&](auto J) {
             constexpr int j = decltype(J)::value;
+            constexpr int every = (STEP - BPOS) / (TM + TN);
             acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.a[j / TN], f1.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
-            if constexpr ((j & 1) == 0) read_one(f0, 0, (j - 32) >> 1);
-            if constexpr (slot(j - 32, N3, 32) >= 0) issue_one(N2B + slot(j - 32, N3, 32));
+            if constexpr ((j - BPOS) % every == 0 && (j - BPOS) / every < TM + TN) read_one(f0, 0, (j - BPOS) / every);
+            if constexpr (slot(j - BPOS, N3, STEP - BPOS) >= 0) issue_one(N2B + slot(j - BPOS, N3, STEP - BPOS));
             __builtin_amdgcn_sched_barrier(0);
         });
     };
