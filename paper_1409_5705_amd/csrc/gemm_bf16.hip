@@ -37,9 +37,9 @@
 //     slice s+2 may start as soon as every wavefront has read the last fragments
 //     of slice s (after its first k-step: the second step's fragments are read
 //     under the first step's MFMAs) and must have landed three quarters into slice
-//     s+1; they are spread over the three quarters of a slice in between, about
-//     one per five MFMAs (a burst of loads blocks the wavefront in the
-//     memory-issue stage while the MFMA pipe runs dry).  Fragments are
+//     s+1; they are spread over the second half of slice s, one per four MFMAs (a
+//     burst of loads blocks the wavefront in the memory-issue stage while the MFMA
+//     pipe runs dry; loads issued later have too little time left).  Fragments are
 //     double-buffered in registers across the barriers, so the MFMA pipe
 //     does not drain at a slice boundary.  Two workgroup barriers per k-slice.
 //   * The loader permutes the rows of the B tile inside LDS so that the eight
