@@ -244,6 +244,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     const int64_t n_my = (xcd_cnt - wi + per_xcd - 1) / per_xcd;   // tiles of this workgroup
     const int64_t nk = p.K / BK;
     const int64_t S = n_my * nk;                                    // k-slices of this workgroup, all tiles
+    // Order of the 64 MFMAs of a k-step: the outer operand's fragment stays for eight MFMAs, the inner one's changes
+    // with every MFMA.  The operand that is mostly zeros (the samples: A of the forward, B of the apply) is the one
+    // that changes: fewer bits toggle at the matrix pipes' inputs.
+    // (forward 4.24 -> 4.20 ms against the other order, interleaved; the apply does not care)
+    constexpr bool B_OUTER = MODE == MODE_FWD;
+    auto tile_a = [](int j) { return B_OUTER ? j % TM : j / TN; };
+    auto tile_b = [](int j) { return B_OUTER ? j / TM : j % TN; };
 
     auto tile_origin = [&](int64_t ordinal, int64_t& m0, int64_t& n0) {
         const int64_t L = xcd_start + ordinal * per_xcd + wi;
@@ -350,15 +357,15 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     struct Frags {
         bf16x8 a[TM], b[TN];
     };
-    // The i-th fragment read of a k-step, in the order the MFMAs (a outer, b inner) want them: a0, b0..b7, a1..a7.
+    // The i-th fragment read of a k-step, in the order the MFMAs want them: the first fragment of the outer
+    // operand, the eight of the inner one, the other seven of the outer one.
     auto read_one = [&](Frags& f, int ks, int i) {
-        if (i == 0 || i > TN) {
-            const int a = i == 0 ? 0 : i - TN;
-            f.a[a] = *reinterpret_cast<const bf16x8*>(lds_bytes + (ra[a & 3] ^ (64u * ks)) + (a >> 2) * 64 * 128);
-        } else {
-            const int b = i - 1;
-            f.b[b] = *reinterpret_cast<const bf16x8*>(lds_bytes + (rb[b & 3] ^ (64u * ks)) + (b >> 2) * 64 * 128);
-        }
+        const bool outer = i == 0 || i > TN;            // a fragment of the operand of the MFMAs' outer loop
+        const int t = i == 0 ? 0 : (i > TN ? i - TN : i - 1);
+        if (outer != B_OUTER)
+            f.a[t] = *reinterpret_cast<const bf16x8*>(lds_bytes + (ra[t & 3] ^ (64u * ks)) + (t >> 2) * 64 * 128);
+        else
+            f.b[t] = *reinterpret_cast<const bf16x8*>(lds_bytes + (rb[t & 3] ^ (64u * ks)) + (t >> 2) * 64 * 128);
     };
     auto read_frags = [&](Frags& f, int ks) {   // k-step ks (32 of k) of the stage ra / rb point at
 #pragma unroll
@@ -534,9 +541,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
         static_for<0, APOS>([&](auto J) {
             constexpr int j = decltype(J)::value;
             if constexpr (decltype(first_tag)::value)
-                acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[j / TN], f0.b[j % TN], zero, 0, 0, 0);
+                acc[tile_a(j)][tile_b(j)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[tile_a(j)], f0.b[tile_b(j)], zero, 0, 0, 0);
             else
-                acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[j / TN], f0.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
+                acc[tile_a(j)][tile_b(j)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[tile_a(j)], f0.b[tile_b(j)], acc[tile_a(j)][tile_b(j)], 0, 0, 0);
             if constexpr (j < 32 && (j & 1) == 0) read_one(f1, 1, j >> 1);
             if constexpr (j < 32) {
                 if constexpr (slot(j, N0, 32) >= 0) issue_one(N2B + N3 + slot(j, N0, 32));
@@ -552,11 +559,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             constexpr int m = decltype(J)::value, j = m % STEP;
             if constexpr (m < STEP) {
                 if constexpr (decltype(first_tag)::value)
-                    acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[j / TN], f0.b[j % TN], zero, 0, 0, 0);
+                    acc[tile_a(j)][tile_b(j)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[tile_a(j)], f0.b[tile_b(j)], zero, 0, 0, 0);
                 else
-                    acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[j / TN], f0.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
+                    acc[tile_a(j)][tile_b(j)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.a[tile_a(j)], f0.b[tile_b(j)], acc[tile_a(j)][tile_b(j)], 0, 0, 0);
             } else {
-                acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.a[j / TN], f1.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
+                acc[tile_a(j)][tile_b(j)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.a[tile_a(j)], f1.b[tile_b(j)], acc[tile_a(j)][tile_b(j)], 0, 0, 0);
             }
             if constexpr (slot(m - APOS, N2B, STEP + BPOS - APOS) >= 0) issue_one(slot(m - APOS, N2B, STEP + BPOS - APOS));
             __builtin_amdgcn_sched_barrier(0);
@@ -568,7 +575,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
         static_for<BPOS, STEP>([&](auto J) {
             constexpr int j = decltype(J)::value;
             constexpr int every = (STEP - BPOS) / (TM + TN);
-            acc[j / TN][j % TN] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.a[j / TN], f1.b[j % TN], acc[j / TN][j % TN], 0, 0, 0);
+            acc[tile_a(j)][tile_b(j)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.a[tile_a(j)], f1.b[tile_b(j)], acc[tile_a(j)][tile_b(j)], 0, 0, 0);
             if constexpr ((j - BPOS) % every == 0 && (j - BPOS) / every < TM + TN) read_one(f0, 0, (j - BPOS) / every);
             if constexpr (slot(j - BPOS, N3, STEP - BPOS) >= 0) issue_one(N2B + slot(j - BPOS, N3, STEP - BPOS));
             __builtin_amdgcn_sched_barrier(0);
