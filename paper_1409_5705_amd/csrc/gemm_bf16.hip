@@ -93,13 +93,14 @@ constexpr int C_POLICY = 2;
 #ifndef SFB_BPOS
 #define SFB_BPOS 32
 #endif
-// Barrier A after APOS of the 64 MFMAs of a slice's first k-step, barrier B after BPOS of those of the second.
+// Barrier A after APOS of the 64 MFMAs of a slice's first k-step, barrier B after BPOS of those of the second
+// (A at 48, 56 or 64 and B at 16, 32 or 48: within 1 % of each other on both contractions; 64 / 32 is the best step).
 constexpr int APOS = SFB_APOS, BPOS = SFB_BPOS;
 constexpr int SCHED[4] = {SFB_SCHED};
 constexpr int N2B = SCHED[0], N3 = SCHED[1], N0 = SCHED[2], N1 = SCHED[3];
 static_assert(N2B + N3 + N0 + N1 == 16 && N2B >= 0 && N3 >= 0 && N0 >= 0 && N1 >= 0, "16 loads per slice");
 static_assert(APOS >= 40 && APOS <= 64 && (APOS == 64 || N1 == 0) && BPOS >= 0 && BPOS <= 48 && (64 - BPOS) % 16 == 0, "barrier positions");
-constexpr int EPD = 3;                   // epilogue: blocks of C loads in flight + the one being stored (2: +1.5 %, 3 and 5: the same)
+constexpr int EPD = 3;                   // epilogue: blocks of C loads in flight + the one being stored (2: the same; 4 spills)
 
 // MODE_SPLIT: the apply on a matrix stored as two 16-bit planes (see split_from_w_kernel):
 // `shadow` is the high plane, `lo` the low one, C is not touched.
