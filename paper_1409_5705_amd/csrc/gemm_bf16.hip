@@ -26,7 +26,7 @@
 //   * The matrix pipes run at the clock the chip grants, and that clock falls with
 //     the bits that toggle in them: on operands that change, the 16x16x32 form of
 //     the MFMA keeps a higher clock than the 32x32x16 form for the same fragment
-//     bytes from LDS (register-only loops: 1.86 against 1.72 PFLOP/s).  A wavefront's
+//     bytes from LDS (register-only loops: 1.92 against 1.78 PFLOP/s).  A wavefront's
 //     128 x 128 block is therefore 8 x 8 tiles of 16 x 16, 64 MFMAs per 32 of k.
 //   * LDS rows are 128 bytes, the eight 16-byte chunks of a row XOR-swizzled by
 //     a function of the row: conflict-free operand reads, no padding.  A direct
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void
 
     // ---- MFMA side ------------------------------------------------------------
     // 16x16x32 MFMAs: on operands that change, the chip keeps a higher clock with them than with the 32x32x16 form
-    // (register-only loops on pseudo-random bf16 data: 1.86 against 1.72 PFLOP/s; inside this kernel 3.5 %), for
+    // (register-only loops on pseudo-random bf16 data, sfb_peaks: 1.92 against 1.78 PFLOP/s), for
     // the same fragment bytes from LDS: eight A and eight B fragments per 32 of k, 64 MFMAs.
     floatx4 acc[TM][TN];    // defined by the first MFMAs of each tile (zero addend)
 
